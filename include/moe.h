@@ -1,0 +1,166 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) MoE expert-layer library.
+ *
+ * One FFN-group GPU's share of a Mixture-of-Experts layer: top-k gating, the shuffle of
+ * tokens from micro-batch order into expert order, the SwiGLU expert FFNs as grouped
+ * GEMMs (forward and backward), and the gate-weighted reduction back to token order.
+ *
+ * Notation (the paper's symbol table in brackets): T tokens [b*s], d hidden size [H],
+ * E experts, k top-k, f expert hidden size [D_e].  This GPU holds the contiguous expert
+ * slice [e_lo, e_lo+e_cnt) (expert parallelism, background section on distributed
+ * training).  R = number of (token, slot) pairs routed to a local expert.
+ *
+ * Conventions for every entry point
+ *   - All pointers are DEVICE pointers unless marked "host".  All matrices are row-major
+ *     and densely packed.  Integer scalars are host values.
+ *   - dtype is MOE_F32 (float) or MOE_BF16 (bfloat16 storage, fp32 accumulation,
+ *     round-to-nearest-even stores).  It is the type of x/xp/h/o/y and of the weights.
+ *   - The caller owns every buffer.  The library allocates no device memory, keeps no
+ *     pointer past the call and never synchronises with the host: each call only enqueues
+ *     kernels on `stream` (a hipStream_t; NULL = the default stream).  Row counts stay on
+ *     the device (offsets[e_cnt] = R), so a whole layer can be enqueued without a sync.
+ *   - Return value: MOE_OK or an error code.  Arguments are validated on the host before
+ *     anything is launched; on error nothing has been enqueued.  No exception or abort
+ *     crosses this boundary.  Inputs must be finite (NaN/Inf logits: unspecified
+ *     selection, but no out-of-bounds access).
+ *   - T == 0 is legal and a no-op (plan outputs are still written: all offsets zero).
+ */
+#ifndef MOE_MI355X_H
+#define MOE_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void* moe_stream_t; /* hipStream_t */
+
+enum { MOE_OK = 0, MOE_EINVAL = 1, MOE_EUNSUPPORTED = 2, MOE_EWORKSPACE = 3, MOE_EHIP = 4 };
+enum { MOE_F32 = 0, MOE_BF16 = 1 };
+enum { MOE_GATE_SOFTMAX_RENORM = 0, MOE_GATE_SIGMOID_RENORM = 1, MOE_GATE_SOFTMAX = 2 };
+enum { MOE_WS_DISPATCH = 0, MOE_WS_EXPERT_FWD = 1, MOE_WS_EXPERT_BWD = 2 };
+
+/* Limits checked by the entry points (MOE_EUNSUPPORTED beyond them). */
+#define MOE_MAX_EXPERTS 1024 /* E */
+#define MOE_MAX_LOCAL 1024   /* e_cnt */
+#define MOE_MAX_TOPK 64      /* k */
+
+/*
+ * moe_route -- top-k gating (MoE background section: a gate network selects the top-k
+ * experts with the highest probability scores).
+ *
+ *   logits  [T,E] float     router outputs (the router GEMM itself is the caller's)
+ *   topk_idx[T,k] int32     out: global expert ids; slot j = j-th best.  Ranking is on the
+ *                           raw fp32 logits, descending; equal logits (+0 == -0) -> the
+ *                           lower expert id first.
+ *   topk_w  [T,k] float     out: gate weights.  SOFTMAX_RENORM: softmax over all E,
+ *                           renormalised over the k selected; SIGMOID_RENORM: logistic
+ *                           scores renormalised over the k selected; SOFTMAX: softmax over
+ *                           all E, not renormalised.
+ *   counts  [e_cnt] int32   out: number of slots routed to each local expert.
+ * Errors: EINVAL for NULL pointers, T<0, E<=0, k<=0, k>E, slice outside [0,E), unknown
+ * gate_mode; EUNSUPPORTED beyond the limits above.
+ */
+int moe_route(const float* logits, int T, int E, int k, int gate_mode, int e_lo, int e_cnt,
+              int32_t* topk_idx, float* topk_w, int32_t* counts, moe_stream_t stream);
+
+/*
+ * moe_dispatch -- shuffle tokens from micro-batch order to expert order (introduction:
+ * tokens are dispatched from the micro-batch ranking to the expert ranking; the paper's
+ * resource-allocation section counts 2*S*k*H bytes of bf16 per direction for it).
+ *
+ * Plan (reuse_plan == 0): from topk_idx build
+ *   offsets [e_cnt+1] int32  out: exclusive prefix sum of the local counts; offsets[e_cnt]=R
+ *   perm    [cap]     int32  out: perm[r] = flat slot s = t*k + j held by row r; rows are
+ *                            sorted by (local expert, s) -- a stable counting sort, so the
+ *                            result is unique and reproducible.  Entries [R,cap) untouched.
+ *   inv     [T,k]     int32  out: row of slot (t,j), or -1 if its expert is not local.
+ * With reuse_plan == 1 the three arrays are inputs (as written by an earlier call) and
+ * topk_idx may be NULL.
+ * Row move: xp[inv[t,j], :] = x[t, :] * (row_scale ? row_scale[t,j] : 1) for every local
+ * slot.  Rows [R,cap) of xp are left untouched.  The scaled form is the backward of
+ * moe_combine with respect to its input (d_o = gate * dy); the product is formed in fp32
+ * and rounded once.
+ *
+ *   x        [T,d] dtype     tokens (or dy)
+ *   row_scale[T,k] float     NULL or per-slot factor
+ *   xp       [cap,d] dtype   out
+ *   cap                      rows available in xp/perm.  cap >= R is the caller's duty
+ *                            (T*min(k,e_cnt) always suffices).  If R > cap, rows >= cap are
+ *                            dropped (their inv is -1), offsets are clamped to cap and the
+ *                            int32 status word at the start of ws is set to 1 (else 0).
+ *   ws, ws_bytes             device scratch of at least
+ *                            moe_workspace_bytes(MOE_WS_DISPATCH, ...) bytes, 256-byte
+ *                            aligned; only used when reuse_plan == 0.
+ * Errors: EINVAL (NULL, negative sizes, k>MOE_MAX_TOPK, bad slice, unknown dtype),
+ * EUNSUPPORTED (bf16 with d % 8 != 0, fp32 with d % 4 != 0), EWORKSPACE.
+ */
+int moe_dispatch(const void* x, int dtype, int T, int d, int k, const int32_t* topk_idx,
+                 const float* row_scale, int e_lo, int e_cnt, int32_t* offsets, int32_t* perm,
+                 int32_t* inv, int reuse_plan, void* xp, int cap, void* ws, size_t ws_bytes,
+                 moe_stream_t stream);
+
+/*
+ * moe_expert_fwd -- the expert FFNs as grouped GEMMs over expert-contiguous rows
+ * (resource-allocation section: after gating, GroupGEMMs over the k*S routed tokens).
+ * For each local expert e and its rows [offsets[e], offsets[e+1]):
+ *     h1 = xp W1[e];  h3 = xp W3[e];  a = silu(h1) * h3;  o = a W2[e]
+ * with silu(z) = z / (1 + exp(-z)).
+ *
+ *   xp [cap,d]; w1,w3 [e_cnt,d,f]; w2 [e_cnt,f,d] (local slice: index 0 = expert e_lo)
+ *   h1,h3 [cap,f]  out, saved for the backward pass; both NULL = forward only
+ *   o  [cap,d]     out.  Rows >= R of every output are left untouched.
+ *   ws             device scratch (holds a [cap,f]), moe_workspace_bytes(MOE_WS_EXPERT_FWD,..)
+ * bf16 requires d % 64 == 0 and f % 64 == 0; fp32 requires d % 4 == 0 and f % 4 == 0
+ * (EUNSUPPORTED otherwise).  offsets must be non-decreasing with offsets[e_cnt] <= cap.
+ */
+int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
+                   const int32_t* offsets, const void* w1, const void* w3, const void* w2,
+                   void* h1, void* h3, void* o, void* ws, size_t ws_bytes, moe_stream_t stream);
+
+/*
+ * moe_expert_bwd -- backward of moe_expert_fwd (AF-Pipe section: FFN workers run backward
+ * passes and send hidden-state gradients back).  Per expert e, on its rows:
+ *     dA  = d_o W2[e]^T                      dW2[e] = a^T d_o
+ *     dH1 = dA * h3 * silu'(h1)              dH3    = dA * silu(h1)
+ *     dW1[e] = xp^T dH1                      dW3[e] = xp^T dH3
+ *     dxp = dH1 W1[e]^T + dH3 W3[e]^T
+ * with silu'(z) = s(z) (1 + z (1 - s(z))), s the logistic function.
+ *
+ *   xp,h1,h3 as saved by the forward; d_o [cap,d] gradient w.r.t. o
+ *   dxp [cap,d] out; dw1,dw3 [e_cnt,d,f], dw2 [e_cnt,f,d] out (dtype = weight dtype)
+ *   accumulate    0: dw* are overwritten (an expert without rows gets zeros);
+ *                 1: the new gradient is added to the existing contents.
+ *   ws            device scratch (a, dH1, dH3), moe_workspace_bytes(MOE_WS_EXPERT_BWD, ...)
+ * Same shape restrictions as the forward.
+ */
+int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d_o, int dtype,
+                   int cap, int d, int f, int e_cnt, const int32_t* offsets, const void* w1,
+                   const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
+                   int accumulate, void* ws, size_t ws_bytes, moe_stream_t stream);
+
+/*
+ * moe_combine -- gate-weighted reduction back to token order (MoE background section:
+ * the outputs of the active experts are reduced by a weighted sum).
+ *     y[t,:] = sum over j with inv[t,j] >= 0, ascending j, of topk_w[t,j] * o[inv[t,j], :]
+ * accumulated in fp32 and rounded once; tokens without a local slot get zeros.  With
+ * topk_w == NULL every weight is 1 (the backward of the unscaled dispatch: dx from dxp).
+ *   o [rows,d] dtype; inv [T,k]; topk_w [T,k] float or NULL; y [T,d] dtype out.
+ * Every inv entry must be -1 or a valid row of o.
+ */
+int moe_combine(const void* o, int dtype, int T, int d, int k, const int32_t* inv,
+                const float* topk_w, void* y, moe_stream_t stream);
+
+/* Scratch bytes needed by the call named by `which` (MOE_WS_*) at these sizes; 0 on
+ * invalid arguments is never returned for valid ones (at least 256). */
+size_t moe_workspace_bytes(int which, int dtype, int T, int k, int d, int f, int e_cnt, int cap);
+
+/* Static, human-readable text for an error code. */
+const char* moe_error_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_MI355X_H */

@@ -1,0 +1,167 @@
+"""ctypes binding of include/moe.h.  Argument marshalling only.
+
+Every function takes torch CUDA tensors (device memory) and forwards their data pointers,
+the sizes and torch's current HIP stream to the C entry point of the same name.  There is
+no fallback: if libmoe_mi355x.so is missing or a call returns an error code, MoeError is
+raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+MOE_F32, MOE_BF16 = 0, 1
+GATE_SOFTMAX_RENORM, GATE_SIGMOID_RENORM, GATE_SOFTMAX = 0, 1, 2
+WS_DISPATCH, WS_EXPERT_FWD, WS_EXPERT_BWD = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = ("moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
+           "moe_workspace_bytes", "moe_error_string")
+
+
+class MoeError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libmoe_mi355x.so")
+
+
+def load_library():
+    """Load the HIP library (built by __graft_entry__.build() / csrc/build.sh)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise MoeError(f"{path} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(path)
+    c_int, c_void_p, c_size_t = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    lib.moe_route.restype = c_int
+    lib.moe_route.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.moe_dispatch.restype = c_int
+    lib.moe_dispatch.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_int, c_int, c_void_p,
+                                 c_void_p, c_void_p, c_int, c_void_p, c_int, c_void_p, c_size_t, c_void_p]
+    lib.moe_expert_fwd.restype = c_int
+    lib.moe_expert_fwd.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p,
+                                   c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.moe_expert_bwd.restype = c_int
+    lib.moe_expert_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p,
+                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int,
+                                   c_void_p, c_size_t, c_void_p]
+    lib.moe_combine.restype = c_int
+    lib.moe_combine.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.moe_workspace_bytes.restype = c_size_t
+    lib.moe_workspace_bytes.argtypes = [c_int] * 8
+    lib.moe_error_string.restype = ctypes.c_char_p
+    lib.moe_error_string.argtypes = [c_int]
+    _LIB = lib
+    return lib
+
+
+def _check(rc: int, name: str):
+    if rc != 0:
+        raise MoeError(f"{name} failed: {load_library().moe_error_string(rc).decode()} (code {rc})")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return MOE_F32
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    raise MoeError(f"unsupported dtype {t.dtype}")
+
+
+def _need(t, dtype=None, shape=None, name="tensor"):
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous():
+        raise MoeError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise MoeError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise MoeError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def moe_workspace_bytes(which, dtype, T, k, d, f, e_cnt, cap) -> int:
+    return int(load_library().moe_workspace_bytes(which, dtype, T, k, d, f, e_cnt, cap))
+
+
+def moe_route(logits, k, gate_mode, e_lo, e_cnt, topk_idx, topk_w, counts):
+    import torch
+    T, E = logits.shape
+    _need(logits, torch.float32, name="logits")
+    _need(topk_idx, torch.int32, (T, k), "topk_idx")
+    _need(topk_w, torch.float32, (T, k), "topk_w")
+    _need(counts, torch.int32, (e_cnt,), "counts")
+    _check(load_library().moe_route(_ptr(logits), T, E, k, gate_mode, e_lo, e_cnt, _ptr(topk_idx), _ptr(topk_w),
+                                    _ptr(counts), _stream()), "moe_route")
+
+
+def moe_dispatch(x, k, topk_idx, row_scale, e_lo, e_cnt, offsets, perm, inv, reuse_plan, xp, ws):
+    import torch
+    T, d = x.shape
+    cap = xp.shape[0]
+    _need(x, name="x"); _need(xp, x.dtype, (cap, d), "xp")
+    _need(topk_idx, torch.int32, (T, k), "topk_idx")
+    _need(row_scale, torch.float32, (T, k), "row_scale")
+    _need(offsets, torch.int32, (e_cnt + 1,), "offsets")
+    _need(perm, torch.int32, (cap,), "perm")
+    _need(inv, torch.int32, (T, k), "inv")
+    _need(ws, name="ws")
+    _check(load_library().moe_dispatch(_ptr(x), _dtype_code(x), T, d, k, _ptr(topk_idx), _ptr(row_scale), e_lo, e_cnt,
+                                       _ptr(offsets), _ptr(perm), _ptr(inv), int(reuse_plan), _ptr(xp), cap,
+                                       _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()),
+           "moe_dispatch")
+
+
+def moe_expert_fwd(xp, offsets, w1, w3, w2, h1, h3, o, ws):
+    import torch
+    cap, d = xp.shape
+    e_cnt, _, f = w1.shape
+    _need(xp, name="xp"); _need(o, xp.dtype, (cap, d), "o")
+    _need(w1, xp.dtype, (e_cnt, d, f), "w1"); _need(w3, xp.dtype, (e_cnt, d, f), "w3")
+    _need(w2, xp.dtype, (e_cnt, f, d), "w2")
+    _need(h1, xp.dtype, (cap, f), "h1"); _need(h3, xp.dtype, (cap, f), "h3")
+    _need(offsets, torch.int32, (e_cnt + 1,), "offsets"); _need(ws, name="ws")
+    _check(load_library().moe_expert_fwd(_ptr(xp), _dtype_code(xp), cap, d, f, e_cnt, _ptr(offsets), _ptr(w1), _ptr(w3),
+                                         _ptr(w2), _ptr(h1), _ptr(h3), _ptr(o), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream()), "moe_expert_fwd")
+
+
+def moe_expert_bwd(xp, h1, h3, d_o, offsets, w1, w3, w2, dxp, dw1, dw3, dw2, accumulate, ws):
+    import torch
+    cap, d = xp.shape
+    e_cnt, _, f = w1.shape
+    dt = xp.dtype
+    _need(xp, name="xp"); _need(h1, dt, (cap, f), "h1"); _need(h3, dt, (cap, f), "h3")
+    _need(d_o, dt, (cap, d), "d_o"); _need(dxp, dt, (cap, d), "dxp")
+    _need(w1, dt, (e_cnt, d, f), "w1"); _need(w3, dt, (e_cnt, d, f), "w3"); _need(w2, dt, (e_cnt, f, d), "w2")
+    _need(dw1, dt, (e_cnt, d, f), "dw1"); _need(dw3, dt, (e_cnt, d, f), "dw3"); _need(dw2, dt, (e_cnt, f, d), "dw2")
+    _need(offsets, torch.int32, (e_cnt + 1,), "offsets"); _need(ws, name="ws")
+    _check(load_library().moe_expert_bwd(_ptr(xp), _ptr(h1), _ptr(h3), _ptr(d_o), _dtype_code(xp), cap, d, f, e_cnt,
+                                         _ptr(offsets), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(dxp), _ptr(dw1), _ptr(dw3),
+                                         _ptr(dw2), int(accumulate), _ptr(ws), ws.numel() * ws.element_size(),
+                                         _stream()), "moe_expert_bwd")
+
+
+def moe_combine(o, inv, topk_w, y):
+    import torch
+    T, k = inv.shape
+    d = o.shape[1]
+    _need(o, name="o"); _need(y, o.dtype, (T, d), "y")
+    _need(inv, torch.int32, name="inv"); _need(topk_w, torch.float32, (T, k), "topk_w")
+    _check(load_library().moe_combine(_ptr(o), _dtype_code(o), T, d, k, _ptr(inv), _ptr(topk_w), _ptr(y), _stream()),
+           "moe_combine")

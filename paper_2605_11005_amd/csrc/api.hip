@@ -1,0 +1,158 @@
+// The C ABI (include/moe.h): argument validation on the host, then kernel launches.
+#include "kernels.h"
+
+#include <mutex>
+
+namespace {
+
+inline bool bad_dtype(int dtype) { return dtype != MOE_F32 && dtype != MOE_BF16; }
+inline size_t esize(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+int shape_check_expert(int dtype, int cap, int d, int f, int e_cnt) {
+  if (bad_dtype(dtype) || cap < 0 || d <= 0 || f <= 0 || e_cnt < 0) return MOE_EINVAL;
+  if (e_cnt > MOE_MAX_LOCAL) return MOE_EUNSUPPORTED;
+  if (dtype == MOE_BF16 && (d % 64 || f % 64)) return MOE_EUNSUPPORTED;
+  if (dtype == MOE_F32 && (d % 4 || f % 4)) return MOE_EUNSUPPORTED;
+  // 32-bit row*ld products inside a tile and 31-bit element counts per activation tensor
+  if ((long long)cap * (d > f ? d : f) >= (1ll << 40)) return MOE_EUNSUPPORTED;
+  if ((long long)(d > f ? d : f) * 256 >= (1ll << 31)) return MOE_EUNSUPPORTED;
+  return MOE_OK;
+}
+
+}  // namespace
+
+int device_cu_count() {
+  static int cached[64];
+  static std::once_flag once;
+  std::call_once(once, [] { for (int& c : cached) c = 0; });
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+extern "C" {
+
+const char* moe_error_string(int code) {
+  switch (code) {
+    case MOE_OK: return "ok";
+    case MOE_EINVAL: return "invalid argument";
+    case MOE_EUNSUPPORTED: return "unsupported shape or size";
+    case MOE_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case MOE_EHIP: return "HIP launch failed";
+    default: return "unknown error code";
+  }
+}
+
+size_t moe_workspace_bytes(int which, int dtype, int T, int k, int d, int f, int e_cnt, int cap) {
+  (void)d;
+  if (T < 0 || k < 0 || f < 0 || e_cnt < 0 || cap < 0) return 256;
+  switch (which) {
+    case MOE_WS_DISPATCH: return align256(plan_ws_bytes(T, k, e_cnt));
+    case MOE_WS_EXPERT_FWD:   // a [cap,f] (+ h1, h3 when the caller does not keep them, fp32 path)
+      return align256((dtype == MOE_F32 ? 3 : 1) * (size_t)cap * f * esize(dtype)) + 256;
+    case MOE_WS_EXPERT_BWD:   // a, dH1, dH3 [cap,f]
+      return align256(3 * (size_t)cap * f * esize(dtype)) + 256;
+    default: return 256;
+  }
+}
+
+int moe_route(const float* logits, int T, int E, int k, int gate_mode, int e_lo, int e_cnt,
+              int32_t* topk_idx, float* topk_w, int32_t* counts, moe_stream_t stream) {
+  if (T < 0 || E <= 0 || k <= 0 || k > E || e_lo < 0 || e_cnt < 0 || e_lo + (long long)e_cnt > E) return MOE_EINVAL;
+  if (gate_mode != MOE_GATE_SOFTMAX_RENORM && gate_mode != MOE_GATE_SIGMOID_RENORM && gate_mode != MOE_GATE_SOFTMAX)
+    return MOE_EINVAL;
+  if (E > MOE_MAX_EXPERTS || e_cnt > MOE_MAX_LOCAL || k > MOE_MAX_TOPK) return MOE_EUNSUPPORTED;
+  if ((long long)T * k >= (1ll << 31) || (long long)T * E >= (1ll << 40)) return MOE_EUNSUPPORTED;
+  if (e_cnt > 0 && !counts) return MOE_EINVAL;
+  if (T > 0 && (!logits || !topk_idx || !topk_w)) return MOE_EINVAL;
+  return launch_route(logits, T, E, k, gate_mode, e_lo, e_cnt, topk_idx, topk_w, counts, (hipStream_t)stream);
+}
+
+int moe_dispatch(const void* x, int dtype, int T, int d, int k, const int32_t* topk_idx,
+                 const float* row_scale, int e_lo, int e_cnt, int32_t* offsets, int32_t* perm,
+                 int32_t* inv, int reuse_plan, void* xp, int cap, void* ws, size_t ws_bytes,
+                 moe_stream_t stream) {
+  if (bad_dtype(dtype) || T < 0 || d <= 0 || k <= 0 || e_lo < 0 || e_cnt < 0 || cap < 0) return MOE_EINVAL;
+  if (k > MOE_MAX_TOPK || e_cnt > MOE_MAX_LOCAL) return MOE_EUNSUPPORTED;
+  if ((long long)T * k >= (1ll << 31)) return MOE_EUNSUPPORTED;
+  if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
+  if (!offsets) return MOE_EINVAL;
+  if (T > 0 && (!x || !inv)) return MOE_EINVAL;
+  if (cap > 0 && (!xp || !perm)) return MOE_EINVAL;
+  if (misaligned(x, 16) || misaligned(xp, 16)) return MOE_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (!reuse_plan) {
+    if (T > 0 && !topk_idx) return MOE_EINVAL;
+    if (!ws || misaligned(ws, 256) || ws_bytes < plan_ws_bytes(T, k, e_cnt)) return MOE_EWORKSPACE;
+    int rc = launch_plan(topk_idx, T, k, e_lo, e_cnt, offsets, perm, inv, cap, ws, s);
+    if (rc) return rc;
+  }
+  return launch_dispatch_rows(x, dtype, T, d, k, inv, row_scale, xp, s);
+}
+
+int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
+                   const int32_t* offsets, const void* w1, const void* w3, const void* w2,
+                   void* h1, void* h3, void* o, void* ws, size_t ws_bytes, moe_stream_t stream) {
+  int rc = shape_check_expert(dtype, cap, d, f, e_cnt);
+  if (rc) return rc;
+  if (!offsets) return MOE_EINVAL;
+  if ((h1 == nullptr) != (h3 == nullptr)) return MOE_EINVAL;
+  if (e_cnt > 0 && (!w1 || !w3 || !w2)) return MOE_EINVAL;
+  if (cap > 0 && (!xp || !o)) return MOE_EINVAL;
+  if (misaligned(xp, 16) || misaligned(o, 16) || misaligned(h1, 16) || misaligned(h3, 16) ||
+      misaligned(w1, 16) || misaligned(w3, 16) || misaligned(w2, 16))
+    return MOE_EINVAL;
+  if (!ws || misaligned(ws, 256) || ws_bytes < moe_workspace_bytes(MOE_WS_EXPERT_FWD, dtype, 0, 0, d, f, e_cnt, cap))
+    return MOE_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == MOE_BF16)
+    return launch_expert_fwd_bf16(xp, cap, d, f, e_cnt, offsets, w1, w3, w2, h1, h3, o, ws, s);
+  float* a = (float*)ws;
+  float* t1 = h1 ? (float*)h1 : a + (size_t)cap * f;
+  float* t3 = h3 ? (float*)h3 : a + 2 * (size_t)cap * f;
+  return launch_expert_fwd_f32((const float*)xp, cap, d, f, e_cnt, offsets, (const float*)w1, (const float*)w3,
+                               (const float*)w2, t1, t3, (float*)o, a, s);
+}
+
+int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d_o, int dtype,
+                   int cap, int d, int f, int e_cnt, const int32_t* offsets, const void* w1,
+                   const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
+                   int accumulate, void* ws, size_t ws_bytes, moe_stream_t stream) {
+  int rc = shape_check_expert(dtype, cap, d, f, e_cnt);
+  if (rc) return rc;
+  if (!offsets || (accumulate != 0 && accumulate != 1)) return MOE_EINVAL;
+  if (e_cnt > 0 && (!w1 || !w3 || !w2 || !dw1 || !dw3 || !dw2)) return MOE_EINVAL;
+  if (cap > 0 && (!xp || !h1 || !h3 || !d_o || !dxp)) return MOE_EINVAL;
+  if (misaligned(xp, 16) || misaligned(h1, 16) || misaligned(h3, 16) || misaligned(d_o, 16) ||
+      misaligned(dxp, 16) || misaligned(w1, 16) || misaligned(w3, 16) || misaligned(w2, 16) ||
+      misaligned(dw1, 16) || misaligned(dw3, 16) || misaligned(dw2, 16))
+    return MOE_EINVAL;
+  if (!ws || misaligned(ws, 256) || ws_bytes < moe_workspace_bytes(MOE_WS_EXPERT_BWD, dtype, 0, 0, d, f, e_cnt, cap))
+    return MOE_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == MOE_BF16)
+    return launch_expert_bwd_bf16(xp, h1, h3, d_o, cap, d, f, e_cnt, offsets, w1, w3, w2, dxp, dw1, dw3, dw2,
+                                  accumulate, ws, s);
+  return launch_expert_bwd_f32((const float*)xp, (const float*)h1, (const float*)h3, (const float*)d_o, cap, d, f,
+                               e_cnt, offsets, (const float*)w1, (const float*)w3, (const float*)w2, (float*)dxp,
+                               (float*)dw1, (float*)dw3, (float*)dw2, accumulate, (float*)ws, s);
+}
+
+int moe_combine(const void* o, int dtype, int T, int d, int k, const int32_t* inv,
+                const float* topk_w, void* y, moe_stream_t stream) {
+  if (bad_dtype(dtype) || T < 0 || d <= 0 || k <= 0) return MOE_EINVAL;
+  if (k > MOE_MAX_TOPK) return MOE_EUNSUPPORTED;
+  if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
+  if (T > 0 && (!inv || !y)) return MOE_EINVAL;
+  if (misaligned(o, 16) || misaligned(y, 16)) return MOE_EINVAL;
+  return launch_combine_rows(o, dtype, T, d, k, inv, topk_w, y, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,7 @@
+#!/bin/bash
+# Builds libmoe_mi355x.so for gfx950 (run from anywhere; output lands next to the package).
+set -e
+cd "$(dirname "$0")"
+exec hipcc --offload-arch=gfx950 -O3 -std=c++17 -fPIC -shared \
+  -Xclang -target-feature -Xclang -packed-fp32-ops "$@" \
+  api.hip route.hip plan.hip rowmove.hip expert_f32.hip expert_bf16.hip -o ../libmoe_mi355x.so

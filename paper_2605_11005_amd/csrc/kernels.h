@@ -1,0 +1,37 @@
+// Internal launch functions behind the C ABI (one per kernel family).  Arguments have been
+// validated by api.hip; every function only enqueues work on `s` and returns a MOE_* code.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include "../../include/moe.h"
+
+int launch_route(const float* logits, int T, int E, int k, int gate_mode, int e_lo, int e_cnt,
+                 int32_t* topk_idx, float* topk_w, int32_t* counts, hipStream_t s);
+
+size_t plan_ws_bytes(int T, int k, int e_cnt);
+int launch_plan(const int32_t* topk_idx, int T, int k, int e_lo, int e_cnt, int32_t* offsets,
+                int32_t* perm, int32_t* inv, int cap, void* ws, hipStream_t s);
+
+int launch_dispatch_rows(const void* x, int dtype, int T, int d, int k, const int32_t* inv,
+                         const float* row_scale, void* xp, hipStream_t s);
+int launch_combine_rows(const void* o, int dtype, int T, int d, int k, const int32_t* inv,
+                        const float* topk_w, void* y, hipStream_t s);
+
+int launch_expert_fwd_f32(const float* xp, int cap, int d, int f, int e_cnt, const int32_t* offsets,
+                          const float* w1, const float* w3, const float* w2, float* h1, float* h3,
+                          float* o, float* a_ws, hipStream_t s);
+int launch_expert_bwd_f32(const float* xp, const float* h1, const float* h3, const float* d_o, int cap,
+                          int d, int f, int e_cnt, const int32_t* offsets, const float* w1,
+                          const float* w3, const float* w2, float* dxp, float* dw1, float* dw3,
+                          float* dw2, int accumulate, float* ws, hipStream_t s);
+
+int launch_expert_fwd_bf16(const void* xp, int cap, int d, int f, int e_cnt, const int32_t* offsets,
+                           const void* w1, const void* w3, const void* w2, void* h1, void* h3, void* o,
+                           void* a_ws, hipStream_t s);
+int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const void* d_o, int cap,
+                           int d, int f, int e_cnt, const int32_t* offsets, const void* w1,
+                           const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
+                           int accumulate, void* ws, hipStream_t s);
+
+int device_cu_count();

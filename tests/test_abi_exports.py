@@ -1,0 +1,71 @@
+"""CPU-only checks of the boundary: the library loads and exports every symbol that
+include/moe.h declares, and host-side validation rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_11005_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "moe.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", src)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.lib_path()):
+        import __graft_entry__ as g
+        g.build()
+    return B.load_library()
+
+
+def test_header_declares_the_five_calls():
+    names = _declared()
+    for n in ("moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine"):
+        assert n in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for n in _declared():
+        assert hasattr(lib, n), n
+    assert set(_declared()) == set(B.EXPORTS)
+
+
+def test_error_strings_and_workspace_sizes(lib):
+    assert lib.moe_error_string(0) == b"ok"
+    for c in (1, 2, 3, 4, 99):
+        assert len(lib.moe_error_string(c)) > 0
+    # a [cap,f] bf16 for the forward, three such for the backward
+    assert B.moe_workspace_bytes(B.WS_EXPERT_FWD, B.MOE_BF16, 0, 0, 64, 128, 4, 1000) >= 1000 * 128 * 2
+    assert B.moe_workspace_bytes(B.WS_EXPERT_BWD, B.MOE_BF16, 0, 0, 64, 128, 4, 1000) >= 3 * 1000 * 128 * 2
+    assert B.moe_workspace_bytes(B.WS_DISPATCH, B.MOE_BF16, 1024, 8, 64, 128, 4, 1000) >= 16 * 4 * 4
+
+
+def test_host_validation_rejects_before_launch(lib):
+    """Only calls that fail validation are made here (no GPU needed: nothing is launched)."""
+    P = ctypes.c_void_p
+    fake = P(4096)
+    # k > E, bad slice, unknown gate mode, NULL pointers
+    assert lib.moe_route(fake, 4, 8, 9, 0, 0, 8, fake, fake, fake, None) == 1
+    assert lib.moe_route(fake, 4, 8, 2, 0, 4, 8, fake, fake, fake, None) == 1
+    assert lib.moe_route(fake, 4, 8, 2, 7, 0, 8, fake, fake, fake, None) == 1
+    assert lib.moe_route(None, 4, 8, 2, 0, 0, 8, fake, fake, fake, None) == 1
+    assert lib.moe_route(fake, 4, 4096, 2, 0, 0, 8, fake, fake, fake, None) == 2
+    # dispatch: bf16 rows must be multiples of 16 bytes; workspace required for planning
+    assert lib.moe_dispatch(fake, 1, 4, 12, 2, fake, None, 0, 4, fake, fake, fake, 0, fake, 8, fake, 1 << 20, None) == 2
+    assert lib.moe_dispatch(fake, 1, 4, 16, 2, fake, None, 0, 4, fake, fake, fake, 0, fake, 8, None, 0, None) == 3
+    assert lib.moe_dispatch(fake, 5, 4, 16, 2, fake, None, 0, 4, fake, fake, fake, 0, fake, 8, fake, 1 << 20, None) == 1
+    # experts: bf16 needs d, f multiples of 64; workspace size is checked
+    assert lib.moe_expert_fwd(fake, 1, 8, 96, 64, 2, fake, fake, fake, fake, None, None, fake, fake, 1 << 20, None) == 2
+    assert lib.moe_expert_fwd(fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, None, None, fake, fake, 16, None) == 3
+    assert lib.moe_expert_fwd(fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, None, fake, fake, 1 << 20, None) == 1
+    assert lib.moe_expert_bwd(fake, fake, fake, fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, fake, fake, fake,
+                              2, fake, 1 << 20, None) == 1
+    assert lib.moe_combine(fake, 1, 4, 12, 2, fake, None, fake, None) == 2
+    assert lib.moe_combine(fake, 1, 4, 16, 100, fake, None, fake, None) == 2
