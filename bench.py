@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE expert-layer hot path on one MI355X.
+
+A step = route -> dispatch -> expert forward -> combine -> (backward) scaled dispatch of dY
+-> expert backward -> combine of dXp, all through the C ABI, inputs resident in HBM.
+Prints ONE JSON line: whole-step expert-layer fwd+bwd TFLOP/s (18*R*d*f useful FLOP per
+step, R = realised routed rows), the roofline entry of the dominant grouped-GEMM kernel
+(timed live with HIP events inside the library), HBM figures for dispatch/combine, and the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+HBM_PEAK_GBPS = 8000.0
+
+# useful FLOP per routed row, in units of d*f, of each grouped-GEMM kernel
+GEMM_FLOP_UNITS = dict(up=4, down=2, da=2, dx=4, wg=2, wgd=4)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="dsv3-like-share")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the expert layer; --gpus must be 1 "
+              "(no collectives or multi-GPU sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_11005_amd import binding as B
+    from paper_2605_11005_amd import counters as C
+    from paper_2605_11005_amd import workloads as W
+    from paper_2605_11005_amd.layer import MoeLayerBuffers, run_backward, run_forward, to_device, torch_dtype
+
+    wl = W.BY_NAME[args.workload]
+    bf16 = wl.dtype == "bf16"
+    b = 2 if bf16 else 4
+    B.load_library()
+    torch.cuda.set_device(0)
+
+    t0 = time.time()
+    x = W.tokens(wl)
+    logits = W.router_logits(wl, x)
+    dy = W.out_grad(wl)
+    w1, w3, w2 = W.all_expert_weights(wl, out_bits=bf16)
+    dt = torch_dtype(wl)
+    dev = dict(x=to_device(x, dt), logits=to_device(logits, torch.float32), dy=to_device(dy, dt),
+               w1=to_device(w1, dt, bf16), w3=to_device(w3, dt, bf16), w2=to_device(w2, dt, bf16))
+    del w1, w3, w2
+    gen_s = time.time() - t0
+
+    # realised row count (outside the timed region) sizes the expert-order buffers
+    cnt = torch.empty((wl.e_cnt,), dtype=torch.int32, device="cuda")
+    ti = torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda")
+    tw = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
+    B.moe_route(dev["logits"], wl.k, wl.gate_mode, wl.e_lo, wl.e_cnt, ti, tw, cnt)
+    counts = cnt.cpu().numpy()
+    R = int(counts.sum())
+    local = ((ti >= wl.e_lo) & (ti < wl.e_lo + wl.e_cnt))
+    U = int(local.any(dim=1).sum().item())
+    del ti, tw, cnt
+    cap = max(R, 1)
+    buf = MoeLayerBuffers(wl, cap=cap)
+
+    def step():
+        run_forward(wl, dev, buf)
+        run_backward(wl, dev, buf)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert buf.status() == 0
+
+    # ---- timed region: exactly K steps, kernels bracketed by events inside the library
+    B.moe_profile_enable(True)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    B.moe_profile_enable(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    d, f, T, k = wl.d, wl.f, wl.T, wl.k
+    flop_step = C.layer_flops(R, d, f)
+    value = flop_step / (ms_per_step * 1e-3) / 1e12
+
+    kern = {}
+    for name in B.KERNEL_IDS:
+        ms, n = B.moe_profile_read(name)
+        if n:
+            kern[name] = dict(avg_ms=ms / n, launches=n)
+    gemm_ms = sum(kern[n]["avg_ms"] * kern[n]["launches"] for n in GEMM_FLOP_UNITS if n in kern) / args.steps
+    for name, units in GEMM_FLOP_UNITS.items():
+        if name in kern:
+            kern[name]["tflops"] = C.gemm_flops(R, d, f, units / 2) / (kern[name]["avg_ms"] * 1e-3) / 1e12
+    # algorithmic bytes of the row movers: dispatch (U+R) rows + index traffic, combine (R+T) rows
+    disp_bytes = C.dispatch_bytes(U, R, T, k, d, b)
+    comb_bytes = C.combine_bytes(R, T, k, d, b)
+    if "dispatch" in kern:
+        kern["dispatch"]["GBps"] = disp_bytes / (kern["dispatch"]["avg_ms"] * 1e-3) / 1e9
+    if "combine" in kern:
+        kern["combine"]["GBps"] = comb_bytes / (kern["combine"]["avg_ms"] * 1e-3) / 1e9
+
+    roofline = None
+    if bf16:
+        dom = max((n for n in GEMM_FLOP_UNITS if n in kern), key=lambda n: kern[n]["avg_ms"])
+        roofline = dict(kernel=f"gg_kernel<{dom.upper()}>", bound="mfma", achieved=kern[dom]["tflops"],
+                        peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=kern[dom]["tflops"] / MFMA_BF16_PEAK_TFLOPS,
+                        traffic=None,
+                        all_gemms_tflops=C.layer_flops(R, d, f) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None)
+    else:
+        # fp32 path: plain FMA tiles on the vector ALUs
+        fl = C.layer_flops(R, d, f)
+        roofline = dict(kernel="fp32 expert GEMMs (all)", bound="alu", achieved=fl / (ms_per_step * 1e-3) / 1e12,
+                        peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=fl / (ms_per_step * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, traffic=None)
+    hbm = {}
+    for name in ("dispatch", "combine"):
+        if name in kern:
+            hbm[name] = dict(bound="hbm", achieved=kern[name]["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
+                             frac=kern[name]["GBps"] / HBM_PEAK_GBPS)
+
+    out = {
+        "metric": "expert-layer fwd+bwd TFLOP/s", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "T": T, "d": d, "E": wl.E, "local_experts": wl.e_cnt, "k": k, "f": f,
+                   "gate_mode": wl.gate_mode, "routed_rows_R": R, "tokens_with_local_slot_U": U,
+                   "rows_per_expert_min_max": [int(counts.min()), int(counts.max())]},
+        "roofline": roofline, "hbm_kernels": hbm, "kernels": kern,
+        "dispatch_combine_GBps": [hbm.get("dispatch", {}).get("achieved"), hbm.get("combine", {}).get("achieved")],
+        "input_generation_s": gen_s,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, x, logits, dy, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl, x, logits, dy, budget_s):
+    """The oracle as it stands, on the host cores: route/plan/dispatch/combine at full size,
+    the expert forward+backward on as many local experts (in id order) as fit the budget."""
+    import numpy as np
+    from oracle import moe_oracle as O
+    from paper_2605_11005_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max((p.get("num_threads", 1) for p in threadpool_info()), default=1)
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    topk_idx, topk_w, counts = O.route(logits, wl.k, wl.gate_mode, wl.e_lo, wl.e_cnt)
+    offsets, perm, inv = O.plan(topk_idx, wl.e_lo, wl.e_cnt)
+    xp = O.dispatch(x, perm, wl.k)
+    d_o = O.dispatch(dy, perm, wl.k, row_scale=topk_w)
+    t_perm = time.perf_counter() - t0
+    flops = 0.0
+    t_exp = 0.0
+    done = []
+    rows = 0
+    for e in range(wl.e_cnt):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo:
+            continue
+        w1, w3, w2 = W.expert_weights(wl, e)
+        off1 = np.array([0, hi - lo], dtype=np.int32)
+        t1 = time.perf_counter()
+        h1, h3, a, o = O.expert_fwd(xp[lo:hi], off1, [w1], [w3], [w2])
+        O.expert_bwd(xp[lo:hi], h1, h3, d_o[lo:hi], off1, [w1], [w3], [w2])
+        t_exp += time.perf_counter() - t1
+        flops += 18.0 * (hi - lo) * wl.d * wl.f
+        rows += hi - lo
+        done.append(e)
+        if t_exp > budget_s:
+            break
+    t2 = time.perf_counter()
+    O.combine(xp, inv, topk_w)
+    t_comb = time.perf_counter() - t2
+    return {"value": flops / t_exp / 1e12 if t_exp else None, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"expert fwd+bwd of local experts {done} ({rows} of {int(offsets[-1])} routed rows) in "
+                      f"{t_exp:.1f} s; route+plan+2 dispatches at full size in {t_perm:.1f} s, one combine in "
+                      f"{t_comb:.1f} s (numpy float64)",
+            "expert_seconds": t_exp, "permute_seconds": t_perm + t_comb}
+
+
+if __name__ == "__main__":
+    main()

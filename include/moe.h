@@ -157,6 +157,26 @@ int moe_combine(const void* o, int dtype, int T, int d, int k, const int32_t* in
  * invalid arguments is never returned for valid ones (at least 256). */
 size_t moe_workspace_bytes(int which, int dtype, int T, int k, int d, int f, int e_cnt, int cap);
 
+/*
+ * Optional per-kernel timing, for benchmarks (measurement of the grouped GEMMs against the
+ * MFMA roofline and of the row movers against HBM bandwidth).  This is the library's only
+ * process-wide state and is off by default.  While enabled, every kernel launch of the
+ * entry points above is bracketed by a pair of hipEvents recorded on the call's stream
+ * (a few microseconds of host work per launch; no synchronisation).
+ *   moe_profile_enable(on)   on != 0: create the event pool (first time) and start recording
+ *                            from an empty log; on == 0: stop recording.
+ *   moe_profile_read(kernel, &total_ms, &launches)
+ *                            synchronises on the recorded events of that kernel (MOE_K_*)
+ *                            and returns the summed elapsed time and the launch count.
+ * The pool holds MOE_PROFILE_MAX_EVENTS launches; later launches are not recorded.
+ * Not thread-safe: enable, run and read from one host thread.
+ */
+enum { MOE_K_ROUTE = 0, MOE_K_PLAN = 1, MOE_K_DISPATCH = 2, MOE_K_COMBINE = 3, MOE_K_UP = 4,
+       MOE_K_DOWN = 5, MOE_K_DA = 6, MOE_K_DX = 7, MOE_K_WG = 8, MOE_K_WGD = 9, MOE_K_COUNT = 10 };
+#define MOE_PROFILE_MAX_EVENTS 8192
+int moe_profile_enable(int on);
+int moe_profile_read(int kernel, double* total_ms /* host */, int* launches /* host */);
+
 /* Static, human-readable text for an error code. */
 const char* moe_error_string(int code);
 

@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
+           "moe_profile_enable", "moe_profile_read",
            "moe_workspace_bytes", "moe_error_string")
 
 
@@ -165,3 +166,23 @@ def moe_combine(o, inv, topk_w, y):
     _need(inv, torch.int32, name="inv"); _need(topk_w, torch.float32, (T, k), "topk_w")
     _check(load_library().moe_combine(_ptr(o), _dtype_code(o), T, d, k, _ptr(inv), _ptr(topk_w), _ptr(y), _stream()),
            "moe_combine")
+
+
+KERNEL_IDS = dict(route=0, plan=1, dispatch=2, combine=3, up=4, down=5, da=6, dx=7, wg=8, wgd=9)
+
+
+def moe_profile_enable(on: bool):
+    lib = load_library()
+    lib.moe_profile_enable.restype = ctypes.c_int
+    lib.moe_profile_enable.argtypes = [ctypes.c_int]
+    _check(lib.moe_profile_enable(int(on)), "moe_profile_enable")
+
+
+def moe_profile_read(kernel: str):
+    """(total milliseconds, launches) recorded for one kernel family since profiling was enabled."""
+    lib = load_library()
+    lib.moe_profile_read.restype = ctypes.c_int
+    lib.moe_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+    ms, n = ctypes.c_double(0), ctypes.c_int(0)
+    _check(lib.moe_profile_read(KERNEL_IDS[kernel], ctypes.byref(ms), ctypes.byref(n)), "moe_profile_read")
+    return ms.value, n.value

@@ -37,7 +37,59 @@ int device_cu_count() {
   return cached[dev];
 }
 
+// ---------------------------------------------------------------- profiling state
+namespace {
+struct ProfLog {
+  bool on = false;
+  bool made = false;
+  int used = 0;
+  hipEvent_t start[MOE_PROFILE_MAX_EVENTS];
+  hipEvent_t stop[MOE_PROFILE_MAX_EVENTS];
+  int kernel[MOE_PROFILE_MAX_EVENTS];
+};
+ProfLog g_prof;
+}  // namespace
+
+ProfScope::ProfScope(int kernel, hipStream_t stream) : slot(-1), s(stream) {
+  if (!g_prof.on || g_prof.used >= MOE_PROFILE_MAX_EVENTS) return;
+  slot = g_prof.used++;
+  g_prof.kernel[slot] = kernel;
+  (void)hipEventRecord(g_prof.start[slot], s);
+}
+ProfScope::~ProfScope() {
+  if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], s);
+}
+
 extern "C" {
+
+int moe_profile_enable(int on) {
+  if (on && !g_prof.made) {
+    for (int i = 0; i < MOE_PROFILE_MAX_EVENTS; ++i)
+      if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess)
+        return MOE_EHIP;
+    g_prof.made = true;
+  }
+  if (on) g_prof.used = 0;
+  g_prof.on = on != 0;
+  return MOE_OK;
+}
+
+int moe_profile_read(int kernel, double* total_ms, int* launches) {
+  if (kernel < 0 || kernel >= MOE_K_COUNT || !total_ms || !launches) return MOE_EINVAL;
+  double sum = 0.0;
+  int n = 0;
+  for (int i = 0; i < g_prof.used; ++i) {
+    if (g_prof.kernel[i] != kernel) continue;
+    if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return MOE_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess) return MOE_EHIP;
+    sum += ms;
+    ++n;
+  }
+  *total_ms = sum;
+  *launches = n;
+  return MOE_OK;
+}
 
 const char* moe_error_string(int code) {
   switch (code) {

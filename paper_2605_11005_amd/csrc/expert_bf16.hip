@@ -457,6 +457,7 @@ int launch_gg(const GArgs& a, hipStream_t s) {
     attr_set = true;
   }
   int grid = device_cu_count();
+  ProfScope prof(MOE_K_UP + MODE, s);
   hipLaunchKernelGGL(gg_kernel<MODE>, dim3(grid), dim3(NT), SMEM_BYTES, s, a);
   HIP_CHECK_LAUNCH();
   return MOE_OK;

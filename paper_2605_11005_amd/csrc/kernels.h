@@ -35,3 +35,11 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
                            int accumulate, void* ws, hipStream_t s);
 
 int device_cu_count();
+
+// Per-kernel timing (moe_profile_*): brackets a launch with events when profiling is on.
+struct ProfScope {
+  int slot;
+  hipStream_t s;
+  ProfScope(int kernel, hipStream_t stream);
+  ~ProfScope();
+};

@@ -119,6 +119,7 @@ size_t plan_ws_bytes(int T, int k, int e_cnt) {
 
 int launch_plan(const int32_t* topk_idx, int T, int k, int e_lo, int e_cnt, int32_t* offsets,
                 int32_t* perm, int32_t* inv, int cap, void* ws, hipStream_t s) {
+  ProfScope prof(MOE_K_PLAN, s);
   int32_t* status = (int32_t*)ws;
   int32_t* ws_hist = (int32_t*)((char*)ws + 256);
   const long long n_slots = (long long)T * k;

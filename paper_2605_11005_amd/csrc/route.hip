@@ -134,6 +134,7 @@ int launch_route(const float* logits, int T, int E, int k, int gate_mode, int e_
     HIP_CHECK_LAUNCH();
   }
   if (T == 0) return MOE_OK;
+  ProfScope prof(MOE_K_ROUTE, s);
   const int wpb = 4;
   int blocks = (T + wpb - 1) / wpb;
   int maxb = device_cu_count() * 8;

@@ -157,6 +157,7 @@ __global__ __launch_bounds__(WPB * WAVE) void combine_rows(const u32x4* __restri
 int launch_dispatch_rows(const void* x, int dtype, int T, int d, int k, const int32_t* inv,
                          const float* row_scale, void* xp, hipStream_t s) {
   if (T == 0) return MOE_OK;
+  ProfScope prof(MOE_K_DISPATCH, s);
   const int row_vecs = dtype == MOE_BF16 ? d / 8 : d / 4;
   dim3 grid((T + WPB - 1) / WPB), block(WPB * WAVE);
   const u32x4* xs = (const u32x4*)x;
@@ -175,6 +176,7 @@ int launch_dispatch_rows(const void* x, int dtype, int T, int d, int k, const in
 int launch_combine_rows(const void* o, int dtype, int T, int d, int k, const int32_t* inv,
                         const float* topk_w, void* y, hipStream_t s) {
   if (T == 0) return MOE_OK;
+  ProfScope prof(MOE_K_COMBINE, s);
   const int row_vecs = dtype == MOE_BF16 ? d / 8 : d / 4;
   dim3 grid((T + WPB - 1) / WPB), block(WPB * WAVE);
   if (dtype == MOE_BF16)
