@@ -8,31 +8,42 @@
 //   WG     dW2   = a^T d_o           ragged K (the expert's rows), both operands read transposed
 //   WGD    dW1|dW3 = xp^T [dH1|dH3]  ragged K, two outputs sharing the A operand
 //
-// Tiling: 256x256x64 block tile, 256 threads = 4 wavefronts in a 2x2 grid, 128x128 per
-// wavefront = 4x4 MFMA blocks (256 accumulator registers), one wavefront per SIMD.
-// Operand tiles live in LDS as [row][64 k] with a 144-byte row pitch (conflict-free 16-byte
-// fragment reads), double buffered: global loads of tile kt+1 are in flight while tile kt
-// feeds the MFMAs; one barrier per k-tile.  Operands whose contraction index is not the
-// contiguous one in memory (weights in the forward, everything in the weight gradients)
-// are transposed in registers (8x8 bf16 blocks) on their way into LDS.
+// Tiling: 256x256 block tile, 32-deep k-tiles, 256 threads = 4 wavefronts in a 2x2 grid,
+// 128x128 per wavefront = 4x4 MFMA blocks (256 accumulator registers), one wavefront per SIMD.
+//
+// Data path: global memory -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
+// staging registers), through a ring of four 32 KB stages, so up to three k-tiles (96 KB per
+// CU) are in flight while one is being multiplied.  Because a wavefront's 64 lanes always
+// land on 1 KB of consecutive LDS, bank conflicts are avoided by choosing WHICH global chunk
+// each lane fetches (an XOR swizzle of the chunk index), not by padding:
+//   K-contiguous operand tile  [256 rows][4 chunks of 8 k]   chunk' = chunk ^ ((row>>1)&3)
+//   transposed operand tile    [32 k][32 chunks of 8 n]      chunk' = chunk ^ (2*(k&3))
+// Operands whose contraction index is not the contiguous one in memory (the weights in the
+// forward pass, both operands of the weight gradients) are kept in their memory layout in
+// LDS and transposed on the way to registers by ds_read_b64_tr_b16.
+// Per k-tile each wavefront runs two k-steps of 16 MFMAs; the fragments of the next k-step
+// are fetched while the current one multiplies, and there is one workgroup barrier per k-tile.
 // Workgroups are persistent and walk a device-built tile list (row counts never visit the
-// host); the list is ordered so that the tiles resident on one XCD share weight panels.
+// host); the list is ordered so that the tiles resident on one XCD share operand panels.
 #include "common.h"
 #include "kernels.h"
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BN = 256, BK = 32;
 constexpr int NT = 256;                 // threads
-constexpr int PITCH = 144;              // bytes per LDS tile row (64 bf16 + 16 B pad)
-constexpr int A_BYTES = BM * PITCH;     // 36864
-constexpr int STAGE_BYTES = (BM + BN) * PITCH;
-constexpr int TILE_LDS = 2 * STAGE_BYTES;          // 147456
-constexpr int SPITCH = 132;             // floats per staging row (128 + 4 pad)
+constexpr int NSTAGE = 4;
+constexpr int OPER_BYTES = 256 * BK * 2;           // 16384: one operand tile
+constexpr int STAGE_BYTES = 2 * OPER_BYTES;        // 32768
+constexpr int TILE_LDS = NSTAGE * STAGE_BYTES;     // 131072
+constexpr int SPITCH = 132;             // floats per epilogue staging row (128 + 4 pad)
 constexpr int SMEM_BYTES = TILE_LDS + (MOE_MAX_LOCAL + 1) * 4;
+static_assert(4 * 32 * SPITCH * 4 <= TILE_LDS, "epilogue staging must fit in the tile ring");
 
 enum { UP = 0, DOWN = 1, DA = 2, DX = 3, WG = 4, WGD = 5 };
 
@@ -61,86 +72,100 @@ template <int MODE> struct Traits {
   static constexpr int BN_EFF = DUAL ? BN / 2 : BN;   // output columns covered per tile
 };
 
-__device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
-
-// 8x8 transpose of bf16: r[i] holds 8 consecutive n at k=i; out[j] holds 8 consecutive k at n=j
-__device__ __forceinline__ void transpose8x8(const uint4 (&r)[8], uint4 (&out)[8]) {
-  const uint32_t* rv = reinterpret_cast<const uint32_t*>(r);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    uint32_t o[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      uint32_t lo = rv[(2 * p) * 4 + j / 2], hi = rv[(2 * p + 1) * 4 + j / 2];
-      o[p] = (j & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
-    }
-    out[j] = make_uint4(o[0], o[1], o[2], o[3]);
-  }
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_wave_base + 16*l
+// (lds_wave_base is wave-uniform and travels in M0).  Written as inline assembly so that the
+// compiler's wait-count pass does not serialise later LDS reads against these loads; the
+// kernel waits for them itself (s_waitcnt vmcnt) before the barrier that publishes a tile.
+__device__ __forceinline__ void dma16(const bf16_t* g, uint32_t lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_wave_base), "v"(g)
+               : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
-// ---- K-contiguous operand: source rows are tile rows, 64 k = 128 contiguous bytes -------
-struct KcLoader {
-  const bf16_t* base;      // &src[row_first * ld]
-  int roff[8];             // element offset of this thread's 8 rows (clamped into range)
-  int kc;                  // 16-byte chunk within the k-tile
-  int r_in;
-  __device__ __forceinline__ void setup(const bf16_t* b, long ld, int rows_valid) {
-    base = b;
-    kc = threadIdx.x & 7;
-    r_in = threadIdx.x >> 3;
+// ---- K-contiguous operand (source rows are tile rows; a k-tile is 64 contiguous bytes) ---
+// Wavefront w issues 4 loads per k-tile; load j covers LDS chunks [(4w+j)*64, +64):
+// row = 16*(4w+j) + lane/4, LDS slot = lane%4, logical chunk = slot ^ ((row>>1)&3).
+// Rows past the valid range re-read the last valid row (their products land in output rows
+// or columns that the epilogue never stores).
+struct KcIssue {
+  const bf16_t* ptr[4];
+  __device__ __forceinline__ void setup(const bf16_t* base, long ld, int rows_valid, int wave, int lane) {
+    const int c = (lane & 3) ^ ((lane >> 3) & 3);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int r = i * 32 + r_in;
-      if (r > rows_valid - 1) r = rows_valid - 1;   // tail rows re-read the last valid row; never stored
-      roff[i] = (int)(r * ld);
+    for (int j = 0; j < 4; ++j) {
+      int r = 16 * (4 * wave + j) + (lane >> 2);
+      if (r > rows_valid - 1) r = rows_valid - 1;
+      ptr[j] = base + (long)r * ld + c * 8;
     }
   }
-  __device__ __forceinline__ void g2r(uint4 (&v)[8], int k0) const {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = ld16(base + roff[i] + k0 + kc * 8);
-  }
-  __device__ __forceinline__ void r2s(const uint4 (&v)[8], char* lds) const {
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<uint4*>(lds + (i * 32 + r_in) * PITCH + kc * 16) = v[i];
+  __device__ __forceinline__ void issue1(int j, uint32_t oper_lds, int wave, long kofs) const {
+    dma16(ptr[j] + kofs, oper_lds + (4 * wave + j) * 1024);
   }
 };
 
-// ---- transposed operand: source is [k][n] with n contiguous; tile rows are n ------------
-struct TrLoader {
-  const bf16_t* base;      // &src[n_first] of this thread's 8-wide n group (already offset), or null
+// ---- transposed operand (source is [k][n], n contiguous; kept as [32 k][256 n] in LDS) ---
+// Load j of wavefront w covers k rows 2*(4w+j) + lane/32, LDS slot = lane%32, logical
+// n chunk = slot ^ (2*(k&3)).  Columns past n_lim are clamped (garbage output columns,
+// never stored); source rows past the last valid one are clamped (the caller zeroes the
+// matching A fragments in the last k-tile).
+struct TrIssue {
+  const bf16_t* rp[4];     // &src[(krow + 2j) * ld + column] for load j (k-tile 0)
   long ld;
-  int q;                   // k group (8 k rows) of this thread
-  int g;                   // n group (8 columns) of this thread, 0..31
-  bool n_ok;
-  __device__ __forceinline__ void setup(const bf16_t* b0, const bf16_t* b1, bool dual, long ld_, int n0, int n_lim) {
-    q = threadIdx.x & 7;
-    g = threadIdx.x >> 3;
+  int krow;                // 8*wave + lane/32: this lane's k row for j = 0
+  __device__ __forceinline__ void setup(const bf16_t* b0, const bf16_t* b1, bool dual, long ld_, int n0, int n_lim,
+                                        int wave, int lane) {
     ld = ld_;
-    int gg = g;
-    const bf16_t* b = b0;
-    if (dual && g >= 16) { gg = g - 16; b = b1; }
-    int n = n0 + gg * 8;
-    n_ok = n < n_lim;
-    base = b + (n_ok ? n : 0);
-  }
-  // k0 = first source row of the k-tile; rows >= k_lim read as zero
-  __device__ __forceinline__ void g2r(uint4 (&v)[8], long k0, long k_lim) const {
+    krow = 8 * wave + (lane >> 5);
+    const bf16_t* col[2];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      long kk = k0 + q * 8 + i;
-      if (n_ok && kk < k_lim) v[i] = ld16(base + kk * ld);
-      else v[i] = make_uint4(0, 0, 0, 0);
+    for (int par = 0; par < 2; ++par) {
+      const int k3 = (2 * par + (lane >> 5)) & 3;
+      int nc = (lane & 31) ^ (2 * k3);
+      const bf16_t* b = b0;
+      if (dual && nc >= 16) { nc -= 16; b = b1; }
+      int n = n0 + nc * 8;
+      if (n > n_lim - 8) n = n_lim - 8;
+      col[par] = b + n;
     }
-  }
-  __device__ __forceinline__ void r2s(const uint4 (&v)[8], char* lds) const {
-    uint4 t[8];
-    transpose8x8(v, t);
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      *reinterpret_cast<uint4*>(lds + (g * 8 + j) * PITCH + q * 16) = t[j];
+    for (int j = 0; j < 4; ++j) rp[j] = col[j & 1];
+  }
+  // load j of the k-tile whose first source row is k0; rows past k_last are clamped if CLAMP
+  template <bool CLAMP>
+  __device__ __forceinline__ void issue1(int j, uint32_t oper_lds, int wave, int k0, int k_last) const {
+    int kk = k0 + krow + 2 * j;
+    if (CLAMP && kk > k_last) kk = k_last;
+    dma16(rp[j] + (long)kk * ld, oper_lds + (4 * wave + j) * 1024);
   }
 };
+
+// Fragment addressing.  MFMA 32x32x16 operand: lane l holds row (l&31), k = 8*(l>>5) + 0..7.
+// K-contiguous tile: one 16-byte read.  byte offset of (row, k-step s) = row*64 + ((2s + (l>>5)) ^ ((row>>1)&3))*16
+// (k-step 1 is k-step 0 with bit 5 flipped: the swizzle is an XOR, not an addition)
+__device__ __forceinline__ int kc_frag_off(int row, int lane, int s) {
+  return row * 64 + (((2 * s + (lane >> 5)) ^ ((row >> 1) & 3)) << 4);
+}
+// Transposed tile: two 8-byte transposing reads (k 0..3 and 4..7 of the lane's group).  Within
+// each group of 16 lanes, lane i supplies the address of T[kb + i/4][nb16 + 4*(i%4) ..+3] and
+// receives T[kb + 0..3][nb16 + i].  Offset for k-step 0, first read; add s*8192 + t*2048.
+__device__ __forceinline__ int tr_frag_off(int nb, int lane) {
+  const int i = lane & 15, g = lane >> 4;
+  const int k = 8 * (g >> 1) + (i >> 2);
+  const int n = nb + 16 * (g & 1) + 4 * (i & 3);
+  return k * 512 + (((n >> 3) ^ (2 * (k & 3))) << 4) + ((n & 4) << 1);
+}
+
+__device__ __forceinline__ bf16x8 lds_frag_kc(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+__device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 2048));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
 
 template <int MODE>
 __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
@@ -150,7 +175,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int e_cnt = p.e_cnt;
 
@@ -187,6 +212,16 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   const int b = blockIdx.x;
   const int first = xcd_ok ? (b % 8) * (G / 8) + b / 8 : b;
 
+  // per-lane fragment offsets inside an operand tile (k-step 0)
+  int a_off[4], b_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int arow = wm * 128 + i * 32;
+    const int brow = TR::DUAL ? (i < 2 ? 0 : 128) + wn * 64 + (i & 1) * 32 : wn * 128 + i * 32;
+    a_off[i] = TR::A_TRANS ? tr_frag_off(arow, lane) : kc_frag_off(arow + (lane & 31), lane, 0);
+    b_off[i] = OPER_BYTES + (TR::B_TRANS ? tr_frag_off(brow, lane) : kc_frag_off(brow + (lane & 31), lane, 0));
+  }
+
   for (int L = first; L < total; L += G) {
     // ---------------------------------------------------------------- decode tile
     int e, lo, hi, mt, nt;
@@ -216,50 +251,49 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     int nk0, nk;            // k-tiles in segment 0 / in total
     int row0;               // first output row (global row for ragged-M, i for WG)
     int row_end;            // one past the last valid output row
-    KcLoader la_kc, lb_kc;
-    TrLoader la_tr, lb_tr;
+    KcIssue ia_kc, ib_kc;
+    TrIssue ia_tr, ib_tr;
     if (TR::RAGGED_K) {
       row0 = mt * BM;
       row_end = p.M;
       nk0 = nk = (hi - lo + BK - 1) / BK;
-      la_tr.setup(p.A0, p.A0, false, p.lda, row0, p.M);
-      lb_tr.setup(p.B0, p.B1, TR::DUAL, p.ldb, n0, p.N);
+      ia_tr.setup(p.A0, p.A0, false, p.lda, row0, p.M, wave, lane);
+      ib_tr.setup(p.B0, p.B1, TR::DUAL, p.ldb, n0, p.N, wave, lane);
     } else {
       row0 = lo + mt * BM;
       row_end = hi;
       nk0 = p.K / BK;
       nk = MODE == DX ? 2 * nk0 : nk0;
-      la_kc.setup(p.A0 + (size_t)row0 * p.lda, p.lda, hi - row0);
-      if (TR::B_TRANS) lb_tr.setup(p.B0 + (size_t)e * p.b_es, p.B1 + (size_t)e * p.b_es, TR::DUAL, p.ldb, n0, p.N);
-      else lb_kc.setup(p.B0 + (size_t)e * p.b_es + (size_t)n0 * p.ldb, p.ldb, p.N - n0);
+      ia_kc.setup(p.A0 + (size_t)row0 * p.lda, p.lda, hi - row0, wave, lane);
+      if (TR::B_TRANS) ib_tr.setup(p.B0 + (size_t)e * p.b_es, p.B1 + (size_t)e * p.b_es, TR::DUAL, p.ldb, n0, p.N, wave, lane);
+      else ib_kc.setup(p.B0 + (size_t)e * p.b_es + (size_t)n0 * p.ldb, p.ldb, p.N - n0, wave, lane);
     }
 
-    auto g2r = [&](uint4 (&va)[8], uint4 (&vb)[8], int kt) {
+    // Issue the loads of k-tile kt (clamped to the last one, so that every iteration issues
+    // the same number of loads and the vmcnt arithmetic below is uniform) into its stage.
+    const uint32_t smem_base = lds_addr(smem);
+    // One of the 8 loads (q = 0..3: operand A, 4..7: operand B) of k-tile kt.  kt is clamped to
+    // the last tile, so every iteration issues the same number of loads and the vmcnt
+    // arithmetic below is uniform; the surplus loads re-fetch the last tile into a free stage.
+    auto issue_one = [&](int kt, int q) {
+      if (kt > nk - 1) kt = nk - 1;
+      const uint32_t st = smem_base + (kt & (NSTAGE - 1)) * STAGE_BYTES;
+      const int j = q & 3;
       if (TR::RAGGED_K) {
-        la_tr.g2r(va, (long)lo + (long)kt * BK, hi);
-        lb_tr.g2r(vb, (long)lo + (long)kt * BK, hi);
+        const int k0 = lo + kt * BK;
+        if (q < 4) ia_tr.template issue1<true>(j, st, wave, k0, hi - 1);
+        else ib_tr.template issue1<true>(j, st + OPER_BYTES, wave, k0, hi - 1);
       } else {
         const bool seg1 = MODE == DX && kt >= nk0;
         const int k0 = (seg1 ? kt - nk0 : kt) * BK;
-        if (seg1) {
-          // second K segment: same row layout, other pointers
-          const long da = p.A1 - p.A0, db = p.B1 - p.B0;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) va[i] = ld16(la_kc.base + da + la_kc.roff[i] + k0 + la_kc.kc * 8);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) vb[i] = ld16(lb_kc.base + db + lb_kc.roff[i] + k0 + lb_kc.kc * 8);
-        } else {
-          la_kc.g2r(va, k0);
-          if (TR::B_TRANS) lb_tr.g2r(vb, k0, p.K);
-          else lb_kc.g2r(vb, k0);
-        }
+        if (q < 4) ia_kc.issue1(j, st, wave, k0 + (seg1 ? p.A1 - p.A0 : 0));
+        else if (TR::B_TRANS) ib_tr.template issue1<false>(j, st + OPER_BYTES, wave, k0, 0);
+        else ib_kc.issue1(j, st + OPER_BYTES, wave, k0 + (seg1 ? p.B1 - p.B0 : 0));
       }
     };
-    auto r2s = [&](const uint4 (&va)[8], const uint4 (&vb)[8], int stage) {
-      char* sa = smem + stage * STAGE_BYTES;
-      char* sb = sa + A_BYTES;
-      if (TR::A_TRANS) la_tr.r2s(va, sa); else la_kc.r2s(va, sa);
-      if (TR::B_TRANS) lb_tr.r2s(vb, sb); else lb_kc.r2s(vb, sb);
+    auto issue_tile = [&](int kt) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) issue_one(kt, q);
     };
 
     f32x16 acc[4][4];
@@ -270,43 +304,79 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // LDS row of this lane's fragment for MFMA block mi / nj
-    const int frag_row = lane & 31, frag_kc = lane >> 5;
-    int a_row[4], b_row[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      a_row[i] = wm * 128 + i * 32 + frag_row;
-      b_row[i] = (TR::DUAL ? (i < 2 ? 0 : 128) + wn * 64 + (i & 1) * 32 : wn * 128 + i * 32) + frag_row;
-    }
-
-    uint4 va[8], vb[8];
-    if (nk > 0) {
-      g2r(va, vb, 0);
-      r2s(va, vb, 0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const bool more = kt + 1 < nk;
-      if (more) g2r(va, vb, kt + 1);
-      const char* sa = smem + (kt & 1) * STAGE_BYTES;
-      const char* sb = sa + A_BYTES;
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 fa[4], fb[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          fa[i] = *reinterpret_cast<const bf16x8*>(sa + a_row[i] * PITCH + (ks * 2 + frag_kc) * 16);
-          fb[i] = *reinterpret_cast<const bf16x8*>(sb + b_row[i] * PITCH + (ks * 2 + frag_kc) * 16);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    // Fragment sets: set h holds the A and B fragments of one k-step.  frag_op(h, kt, s, o)
+    // performs the o-th of the 8 fragment reads of k-step s of tile kt, in the order the
+    // MFMAs consume them: A0, B0, B1, B2, B3, A1, A2, A3.
+    bf16x8 fa[2][4], fb[2][4];
+    auto frag_op = [&](int h, int kt, int s, int o) {
+      const char* st = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
+      const bool is_a = o == 0 || o >= 5;
+      const int idx = o == 0 ? 0 : (o >= 5 ? o - 4 : o - 1);
+      if (is_a) {
+        const char* q = st + (TR::A_TRANS ? a_off[idx] + s * 8192 : a_off[idx] ^ (s * 32));
+        fa[h][idx] = TR::A_TRANS ? lds_frag_tr(q) : lds_frag_kc(q);
+      } else {
+        const char* q = st + (TR::B_TRANS ? b_off[idx] + s * 8192 : b_off[idx] ^ (s * 32));
+        fb[h][idx] = TR::B_TRANS ? lds_frag_tr(q) : lds_frag_kc(q);
       }
-      if (more) r2s(va, vb, (kt + 1) & 1);
+    };
+    auto mfma_one = [&](int h, int m) {
+      const int i = m >> 2, j = m & 3;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[h][i], fb[h][j], acc[i][j], 0, 0, 0);
+    };
+    // ragged contraction: zero the A fragment elements whose source row is past the expert's
+    // last row (only the last k-tile can contain such rows)
+    auto mask_tail = [&](int h, int kt, int s) {
+      const int kbase = lo + kt * BK + 16 * s + 8 * (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        s16x8 v = __builtin_bit_cast(s16x8, fa[h][i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (kbase + j < hi) ? v[j] : (short)0;
+        fa[h][i] = __builtin_bit_cast(bf16x8, v);
+      }
+    };
+
+    // ---- k loop.  Ring of four stages; at the barrier of iteration kt every wavefront has
+    // all fragments of tile kt in registers, so stage kt%4 is free for tile kt+4, and tile
+    // kt+1 (issued three barriers ago) has landed.  Each thread has 8 loads per tile in
+    // flight: tiles kt+1..kt+3 outstanding -> wait until at most 16 remain.
+    // The instruction order inside an iteration is fixed by hand (scheduling fences after every
+    // MFMA pair): 16 MFMAs of k-step 0 with the 8 fragment reads of k-step 1 between them,
+    // barrier, 16 MFMAs of k-step 1 with the next tile's first fragment reads and the 8 loads
+    // of tile kt+4 between them -- everything else issues in the shadow of the MFMAs.
+    if (nk > 0) {
+      issue_tile(0); issue_tile(1); issue_tile(2); issue_tile(3);
+      asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
       __syncthreads();
+#pragma unroll
+      for (int o = 0; o < 8; ++o) frag_op(0, 0, 0, o);
     }
+    for (int kt = 0; kt < nk; ++kt) {
+      if (TR::RAGGED_K && kt == nk - 1) mask_tail(0, kt, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int m = 0; m < 16; m += 2) {
+        mfma_one(0, m);
+        frag_op(1, kt, 1, m >> 1);
+        mfma_one(0, m + 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      if (TR::RAGGED_K && kt == nk - 1) mask_tail(1, kt, 1);
+#pragma unroll
+      for (int m = 0; m < 16; m += 2) {
+        mfma_one(1, m);
+        frag_op(0, kt + 1, 0, m >> 1);
+        mfma_one(1, m + 1);
+        issue_one(kt + 4, m >> 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
 
     // ---------------------------------------------------------------- epilogue
     // Each wavefront stages one 32-row slab of its 128x128 tile in LDS as fp32, then walks it
