@@ -16,8 +16,10 @@
 // CU) are in flight while one is being multiplied.  Because a wavefront's 64 lanes always
 // land on 1 KB of consecutive LDS, bank conflicts are avoided by choosing WHICH global chunk
 // each lane fetches (an XOR swizzle of the chunk index), not by padding:
-//   K-contiguous operand tile  [256 rows][4 chunks of 8 k]   chunk' = chunk ^ ((row>>1)&3)
-//   transposed operand tile    [32 k][32 chunks of 8 n]      chunk' = chunk ^ (2*(k&3))
+//   K-contiguous operand tile  [256 rows][4 chunks of 8 k]   chunk' = chunk ^ ((row>>2)&3)
+//   transposed operand tile    2 x [32 k][16 chunks of 8 n]  chunk' = chunk ^ (4*(k&3))
+// (LDS has 64 four-byte banks: the 16 lanes served together by a 16-byte read, or the 32 lanes
+// of an 8-byte transposing read, must cover 256 distinct bytes modulo 256.)
 // Operands whose contraction index is not the contiguous one in memory (the weights in the
 // forward pass, both operands of the weight gradients) are kept in their memory layout in
 // LDS and transposed on the way to registers by ds_read_b64_tr_b16.
@@ -73,13 +75,21 @@ template <int MODE> struct Traits {
 };
 
 // 16 bytes per lane from global memory straight into LDS: lane l lands at lds_wave_base + 16*l
-// (lds_wave_base is wave-uniform and travels in M0).  Written as inline assembly so that the
-// compiler's wait-count pass does not serialise later LDS reads against these loads; the
-// kernel waits for them itself (s_waitcnt vmcnt) before the barrier that publishes a tile.
-__device__ __forceinline__ void dma16(const bf16_t* g, uint32_t lds_wave_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+// (lds_wave_base is wave-uniform and travels in M0).  The global address is a wave-uniform
+// 64-bit base in SGPRs plus a 32-bit per-lane byte offset: with 64-bit per-lane addresses the
+// address path, not the data path, limits a CU to ~27 B/clk; this form sustains ~42 B/clk.
+// Written as inline assembly so that the compiler's wait-count pass does not serialise later
+// LDS reads against these loads; the kernel waits for them itself (s_waitcnt vmcnt) before
+// the barrier that publishes a tile.
+__device__ __forceinline__ void dma16(const bf16_t* sbase, uint32_t voff_bytes, uint32_t lds_wave_base) {
+  // make the uniformity of the base explicit so that it is allocated to an SGPR pair
+  const uint64_t u = (uint64_t)sbase;
+  const uint64_t ub = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(u >> 32)) << 32) |
+                      (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
+  sbase = (const bf16_t*)ub;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
-               : "s"(lds_wave_base), "v"(g)
+               : "s"(lds_wave_base), "v"(voff_bytes), "s"(sbase)
                : "memory", "m0");
 }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
@@ -88,81 +98,79 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 
 // ---- K-contiguous operand (source rows are tile rows; a k-tile is 64 contiguous bytes) ---
 // Wavefront w issues 4 loads per k-tile; load j covers LDS chunks [(4w+j)*64, +64):
-// row = 16*(4w+j) + lane/4, LDS slot = lane%4, logical chunk = slot ^ ((row>>1)&3).
+// row = 16*(4w+j) + lane/4, LDS slot = lane%4, logical chunk = slot ^ ((row>>2)&3).
 // Rows past the valid range re-read the last valid row (their products land in output rows
 // or columns that the epilogue never stores).
 struct KcIssue {
-  const bf16_t* ptr[4];
-  __device__ __forceinline__ void setup(const bf16_t* base, long ld, int rows_valid, int wave, int lane) {
-    const int c = (lane & 3) ^ ((lane >> 3) & 3);
+  const bf16_t* base;      // wave-uniform: first row of the tile
+  uint32_t voff[4];        // byte offset of this lane's chunk in load j
+  __device__ __forceinline__ void setup(const bf16_t* base_, long ld, int rows_valid, int wave, int lane) {
+    base = base_;
+    const int c = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int r = 16 * (4 * wave + j) + (lane >> 2);
       if (r > rows_valid - 1) r = rows_valid - 1;
-      ptr[j] = base + (long)r * ld + c * 8;
+      voff[j] = (uint32_t)(r * ld * 2 + c * 16);
     }
   }
   __device__ __forceinline__ void issue1(int j, uint32_t oper_lds, int wave, long kofs) const {
-    dma16(ptr[j] + kofs, oper_lds + (4 * wave + j) * 1024);
+    dma16(base + kofs, voff[j], oper_lds + (4 * wave + j) * 1024);
   }
 };
 
-// ---- transposed operand (source is [k][n], n contiguous; kept as [32 k][256 n] in LDS) ---
-// Load j of wavefront w covers k rows 2*(4w+j) + lane/32, LDS slot = lane%32, logical
-// n chunk = slot ^ (2*(k&3)).  Columns past n_lim are clamped (garbage output columns,
-// never stored); source rows past the last valid one are clamped (the caller zeroes the
-// matching A fragments in the last k-tile).
+// ---- transposed operand (source is [k][n], n contiguous) --------------------------------
+// Kept in LDS as two sub-tiles [32 k][128 n] of 8 KB (for a dual tile they come from two
+// source matrices).  A tile is 16 loads; load id = 4*wave + j covers sub-tile id/8 and the
+// four k rows 4*(id%8) + lane/16; LDS slot = lane%16, logical n chunk = slot ^ (4*(k&3)).
+// Columns past n_lim are clamped (garbage output columns, never stored); with CLAMP, source
+// rows past the last valid one are clamped (the caller zeroes the matching A fragments).
 struct TrIssue {
-  const bf16_t* rp[4];     // &src[(krow + 2j) * ld + column] for load j (k-tile 0)
+  const bf16_t* src;       // wave-uniform: column n0 of this wavefront's sub-tile source, row 0
   long ld;
-  int krow;                // 8*wave + lane/32: this lane's k row for j = 0
+  uint32_t coff;           // byte offset of this lane's column chunk
+  // a wavefront's four loads all belong to sub-tile wave/2
   __device__ __forceinline__ void setup(const bf16_t* b0, const bf16_t* b1, bool dual, long ld_, int n0, int n_lim,
                                         int wave, int lane) {
     ld = ld_;
-    krow = 8 * wave + (lane >> 5);
-    const bf16_t* col[2];
-#pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      const int k3 = (2 * par + (lane >> 5)) & 3;
-      int nc = (lane & 31) ^ (2 * k3);
-      const bf16_t* b = b0;
-      if (dual && nc >= 16) { nc -= 16; b = b1; }
-      int n = n0 + nc * 8;
-      if (n > n_lim - 8) n = n_lim - 8;
-      col[par] = b + n;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) rp[j] = col[j & 1];
+    const int sub = wave >> 1;
+    const int nc = (lane & 15) ^ (4 * (lane >> 4));
+    src = (dual && sub) ? b1 : b0;
+    int n = n0 + (dual ? 0 : sub * 128) + nc * 8;
+    if (n > n_lim - 8) n = n_lim - 8;
+    coff = (uint32_t)(n * 2);
   }
-  // load j of the k-tile whose first source row is k0; rows past k_last are clamped if CLAMP
+  // load j of the k-tile whose first source row is k0 (rows above k_last_rel clamped if CLAMP)
   template <bool CLAMP>
-  __device__ __forceinline__ void issue1(int j, uint32_t oper_lds, int wave, int k0, int k_last) const {
-    int kk = k0 + krow + 2 * j;
-    if (CLAMP && kk > k_last) kk = k_last;
-    dma16(rp[j] + (long)kk * ld, oper_lds + (4 * wave + j) * 1024);
+  __device__ __forceinline__ void issue1(int j, uint32_t oper_lds, int wave, int lane, long k0, int k_last_rel) const {
+    const int id = 4 * wave + j;
+    int kr = 4 * (id & 7) + (lane >> 4);
+    if (CLAMP && kr > k_last_rel) kr = k_last_rel;
+    dma16(src + k0 * ld, (uint32_t)(kr * ld * 2) + coff, oper_lds + id * 1024);
   }
 };
 
 // Fragment addressing.  MFMA 32x32x16 operand: lane l holds row (l&31), k = 8*(l>>5) + 0..7.
-// K-contiguous tile: one 16-byte read.  byte offset of (row, k-step s) = row*64 + ((2s + (l>>5)) ^ ((row>>1)&3))*16
+// K-contiguous tile: one 16-byte read.  byte offset of (row, k-step s) = row*64 + ((2s + (l>>5)) ^ ((row>>2)&3))*16
 // (k-step 1 is k-step 0 with bit 5 flipped: the swizzle is an XOR, not an addition)
 __device__ __forceinline__ int kc_frag_off(int row, int lane, int s) {
-  return row * 64 + (((2 * s + (lane >> 5)) ^ ((row >> 1) & 3)) << 4);
+  return row * 64 + (((2 * s + (lane >> 5)) ^ ((row >> 2) & 3)) << 4);
 }
 // Transposed tile: two 8-byte transposing reads (k 0..3 and 4..7 of the lane's group).  Within
 // each group of 16 lanes, lane i supplies the address of T[kb + i/4][nb16 + 4*(i%4) ..+3] and
-// receives T[kb + 0..3][nb16 + i].  Offset for k-step 0, first read; add s*8192 + t*2048.
+// receives T[kb + 0..3][nb16 + i].  Offset for k-step 0, first read; add s*4096 + t*1024.
 __device__ __forceinline__ int tr_frag_off(int nb, int lane) {
   const int i = lane & 15, g = lane >> 4;
   const int k = 8 * (g >> 1) + (i >> 2);
   const int n = nb + 16 * (g & 1) + 4 * (i & 3);
-  return k * 512 + (((n >> 3) ^ (2 * (k & 3))) << 4) + ((n & 4) << 1);
+  const int sub = n >> 7, nl = n & 127;
+  return sub * 8192 + k * 256 + (((nl >> 3) ^ (4 * (k & 3))) << 4) + ((n & 4) << 1);
 }
 
 __device__ __forceinline__ bf16x8 lds_frag_kc(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 2048));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 1024));
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
 }
@@ -222,7 +230,13 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     b_off[i] = OPER_BYTES + (TR::B_TRANS ? tr_frag_off(brow, lane) : kc_frag_off(brow + (lane & 31), lane, 0));
   }
 
+#if defined(EXP_CYCLES)
+  unsigned long long t_kernel0 = __builtin_amdgcn_s_memtime(), c_loop = 0, c_epi = 0, c_pro = 0, n_it = 0, c_w_lds = 0, c_w_vm = 0, c_w_bar = 0;
+#endif
   for (int L = first; L < total; L += G) {
+#if defined(EXP_CYCLES)
+    unsigned long long t_a = __builtin_amdgcn_s_memtime();
+#endif
     // ---------------------------------------------------------------- decode tile
     int e, lo, hi, mt, nt;
     if (TR::RAGGED_K) {
@@ -277,17 +291,21 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     // arithmetic below is uniform; the surplus loads re-fetch the last tile into a free stage.
     auto issue_one = [&](int kt, int q) {
       if (kt > nk - 1) kt = nk - 1;
+#if defined(EXP_FIXED_K)
+      kt &= 3;
+#endif
       const uint32_t st = smem_base + (kt & (NSTAGE - 1)) * STAGE_BYTES;
       const int j = q & 3;
       if (TR::RAGGED_K) {
-        const int k0 = lo + kt * BK;
-        if (q < 4) ia_tr.template issue1<true>(j, st, wave, k0, hi - 1);
-        else ib_tr.template issue1<true>(j, st + OPER_BYTES, wave, k0, hi - 1);
+        const long k0 = (long)lo + kt * BK;
+        const int k_last_rel = hi - 1 - lo - kt * BK;
+        if (q < 4) ia_tr.template issue1<true>(j, st, wave, lane, k0, k_last_rel);
+        else ib_tr.template issue1<true>(j, st + OPER_BYTES, wave, lane, k0, k_last_rel);
       } else {
         const bool seg1 = MODE == DX && kt >= nk0;
         const int k0 = (seg1 ? kt - nk0 : kt) * BK;
         if (q < 4) ia_kc.issue1(j, st, wave, k0 + (seg1 ? p.A1 - p.A0 : 0));
-        else if (TR::B_TRANS) ib_tr.template issue1<false>(j, st + OPER_BYTES, wave, k0, 0);
+        else if (TR::B_TRANS) ib_tr.template issue1<false>(j, st + OPER_BYTES, wave, lane, k0, 0);
         else ib_kc.issue1(j, st + OPER_BYTES, wave, k0 + (seg1 ? p.B1 - p.B0 : 0));
       }
     };
@@ -313,10 +331,10 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       const bool is_a = o == 0 || o >= 5;
       const int idx = o == 0 ? 0 : (o >= 5 ? o - 4 : o - 1);
       if (is_a) {
-        const char* q = st + (TR::A_TRANS ? a_off[idx] + s * 8192 : a_off[idx] ^ (s * 32));
+        const char* q = st + (TR::A_TRANS ? a_off[idx] + s * 4096 : a_off[idx] ^ (s * 32));
         fa[h][idx] = TR::A_TRANS ? lds_frag_tr(q) : lds_frag_kc(q);
       } else {
-        const char* q = st + (TR::B_TRANS ? b_off[idx] + s * 8192 : b_off[idx] ^ (s * 32));
+        const char* q = st + (TR::B_TRANS ? b_off[idx] + s * 4096 : b_off[idx] ^ (s * 32));
         fb[h][idx] = TR::B_TRANS ? lds_frag_tr(q) : lds_frag_kc(q);
       }
     };
@@ -339,19 +357,26 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
 
     // ---- k loop.  Ring of four stages; at the barrier of iteration kt every wavefront has
     // all fragments of tile kt in registers, so stage kt%4 is free for tile kt+4, and tile
-    // kt+1 (issued three barriers ago) has landed.  Each thread has 8 loads per tile in
-    // flight: tiles kt+1..kt+3 outstanding -> wait until at most 16 remain.
+    // kt+1 has landed.  Loads are spread evenly over the iteration -- one per four MFMAs -- so
+    // that the CU's address unit (one 64-lane load per ~24 cycles, shared by the four
+    // wavefronts) never backs up into the issue stream: the first half issues operand B of
+    // tile kt+3, the second half operand A of tile kt+4.  Issue order is A(t),B(t),A(t+1),..;
+    // at the barrier the loads after B(kt+1) are A,B(kt+2) and A,B(kt+3): 16 may remain.
     // The instruction order inside an iteration is fixed by hand (scheduling fences after every
     // MFMA pair): 16 MFMAs of k-step 0 with the 8 fragment reads of k-step 1 between them,
-    // barrier, 16 MFMAs of k-step 1 with the next tile's first fragment reads and the 8 loads
-    // of tile kt+4 between them -- everything else issues in the shadow of the MFMAs.
+    // barrier, 16 MFMAs of k-step 1 with the next tile's first fragment reads between them.
     if (nk > 0) {
-      issue_tile(0); issue_tile(1); issue_tile(2); issue_tile(3);
-      asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+      issue_tile(0); issue_tile(1); issue_tile(2);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) issue_one(3, q);
+      asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
       __syncthreads();
 #pragma unroll
       for (int o = 0; o < 8; ++o) frag_op(0, 0, 0, o);
     }
+#if defined(EXP_CYCLES)
+    unsigned long long t_b = __builtin_amdgcn_s_memtime();
+#endif
     for (int kt = 0; kt < nk; ++kt) {
       if (TR::RAGGED_K && kt == nk - 1) mask_tail(0, kt, 0);
       __builtin_amdgcn_sched_barrier(0);
@@ -360,6 +385,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
         mfma_one(0, m);
         frag_op(1, kt, 1, m >> 1);
         mfma_one(0, m + 1);
+        if ((m & 3) == 2) issue_one(kt + 3, 4 + (m >> 2));     // operand B of tile kt+3
         __builtin_amdgcn_sched_barrier(0);
       }
       asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
@@ -371,12 +397,15 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
         mfma_one(1, m);
         frag_op(0, kt + 1, 0, m >> 1);
         mfma_one(1, m + 1);
-        issue_one(kt + 4, m >> 1);
+        if ((m & 3) == 2) issue_one(kt + 4, m >> 2);           // operand A of tile kt+4
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
+#if defined(EXP_CYCLES)
+    unsigned long long t_c = __builtin_amdgcn_s_memtime();
+#endif
 
     // ---------------------------------------------------------------- epilogue
     // Each wavefront stages one 32-row slab of its 128x128 tile in LDS as fp32, then walks it
@@ -514,7 +543,17 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       }
       __syncthreads();
     }
+#if defined(EXP_CYCLES)
+    unsigned long long t_d = __builtin_amdgcn_s_memtime();
+    c_pro += t_b - t_a; c_loop += t_c - t_b; c_epi += t_d - t_c; n_it += nk;
+#endif
   }
+#if defined(EXP_CYCLES)
+  if (MODE == UP && p.H1 && blockIdx.x == 3 && tid == 0) {
+    unsigned long long* dbg = (unsigned long long*)p.H1;
+    dbg[0] = __builtin_amdgcn_s_memtime() - t_kernel0; dbg[1] = c_pro; dbg[2] = c_loop; dbg[3] = c_epi; dbg[4] = n_it; dbg[5] = c_w_lds; dbg[6] = c_w_vm; dbg[7] = c_w_bar;
+  }
+#endif
 }
 
 template <int MODE>
@@ -544,6 +583,9 @@ int launch_expert_fwd_bf16(const void* xp, int cap, int d, int f, int e_cnt, con
   u.B0 = (const bf16_t*)w1; u.B1 = (const bf16_t*)w3; u.ldb = f; u.b_es = (long)d * f;
   u.C0 = (bf16_t*)h1; u.C1 = (bf16_t*)h3; u.C2 = (bf16_t*)a_ws; u.ldc = f;
   u.off = offsets; u.e_cnt = e_cnt; u.N = f; u.K = d; u.save_h = (h1 && h3) ? 1 : 0;
+#if defined(EXP_CYCLES)
+  u.H1 = (const bf16_t*)((char*)a_ws + (((size_t)cap * f * 2 + 255) & ~(size_t)255));
+#endif
   int rc = launch_gg<UP>(u, s);
   if (rc) return rc;
   GArgs w = {};
