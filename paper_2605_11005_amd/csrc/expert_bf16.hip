@@ -44,7 +44,7 @@ constexpr int OPER_BYTES = 256 * BK * 2;           // 16384: one operand tile
 constexpr int STAGE_BYTES = 2 * OPER_BYTES;        // 32768
 constexpr int TILE_LDS = NSTAGE * STAGE_BYTES;     // 131072
 constexpr int SPITCH = 132;             // floats per epilogue staging row (128 + 4 pad)
-constexpr int SMEM_BYTES = TILE_LDS + (MOE_MAX_LOCAL + 1) * 4;
+constexpr int SMEM_BYTES = TILE_LDS + 2 * (MOE_MAX_LOCAL + 1) * 4;   // + tile_start[], offs[]
 static_assert(4 * 32 * SPITCH * 4 <= TILE_LDS, "epilogue staging must fit in the tile ring");
 
 enum { UP = 0, DOWN = 1, DA = 2, DX = 3, WG = 4, WGD = 5 };
@@ -180,6 +180,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   using TR = Traits<MODE>;
   extern __shared__ __align__(16) char smem[];
   int32_t* tile_start = reinterpret_cast<int32_t*>(smem + TILE_LDS);
+  int32_t* offs = tile_start + (MOE_MAX_LOCAL + 1);      // LDS copy of the row offsets
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -190,6 +191,8 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   const int n_tiles_n = (p.N + TR::BN_EFF - 1) / TR::BN_EFF;
   int total;
   int wg_tiles_per_e = 0, wg_mt = 0;
+  for (int e = tid; e <= e_cnt; e += NT) offs[e] = p.off[e];
+  __syncthreads();
   if (TR::RAGGED_K) {
     wg_mt = (p.M + BM - 1) / BM;
     wg_tiles_per_e = wg_mt * n_tiles_n;
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   } else {
     // tile_start[e] = number of tiles before expert e
     for (int e = tid; e < e_cnt; e += NT) {
-      int rows = p.off[e + 1] - p.off[e];
+      int rows = offs[e + 1] - offs[e];
       tile_start[e] = ((rows + BM - 1) / BM) * n_tiles_n;
     }
     __syncthreads();
@@ -238,27 +241,35 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     unsigned long long t_a = __builtin_amdgcn_s_memtime();
 #endif
     // ---------------------------------------------------------------- decode tile
+    // Within an expert, tiles are ordered in bands of 8 m-tiles, n-tile next, m-tile inside the
+    // band fastest: 32 consecutive tiles (one XCD's share of a round) then form an 8 x 4 block
+    // that shares 8 A panels and 4 B panels through that XCD's L2.
     int e, lo, hi, mt, nt;
-    if (TR::RAGGED_K) {
-      e = L / wg_tiles_per_e;
-      int li = L - e * wg_tiles_per_e;
-      mt = li % wg_mt;
-      nt = li / wg_mt;
-      lo = p.off[e];
-      hi = p.off[e + 1];
-    } else {
-      int a = 0, c = e_cnt;                    // largest e with tile_start[e] <= L
-      while (c - a > 1) {
-        int mid = (a + c) >> 1;
-        if (tile_start[mid] <= L) a = mid; else c = mid;
+    {
+      int li, mte;
+      if (TR::RAGGED_K) {
+        e = L / wg_tiles_per_e;
+        li = L - e * wg_tiles_per_e;
+        mte = wg_mt;
+      } else {
+        int a = 0, c = e_cnt;                    // largest e with tile_start[e] <= L
+        while (c - a > 1) {
+          int mid = (a + c) >> 1;
+          if (tile_start[mid] <= L) a = mid; else c = mid;
+        }
+        e = a;
+        li = L - tile_start[e];
+        mte = 0;
       }
-      e = a;
-      lo = p.off[e];
-      hi = p.off[e + 1];
-      int mte = (hi - lo + BM - 1) / BM;
-      int li = L - tile_start[e];
-      mt = li % mte;
-      nt = li / mte;
+      e = __builtin_amdgcn_readfirstlane(e);
+      lo = __builtin_amdgcn_readfirstlane(offs[e]);
+      hi = __builtin_amdgcn_readfirstlane(offs[e + 1]);
+      if (!TR::RAGGED_K) mte = (hi - lo + BM - 1) / BM;
+      const int band = li / (8 * n_tiles_n);
+      const int in_band = li - band * 8 * n_tiles_n;
+      const int band_rows = min(8, mte - band * 8);
+      nt = in_band / band_rows;
+      mt = band * 8 + (in_band - nt * band_rows);
     }
     const int n0 = nt * TR::BN_EFF;
 
@@ -383,7 +394,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
 #pragma unroll
       for (int m = 0; m < 16; m += 2) {
         mfma_one(0, m);
-        frag_op(1, kt, 1, m >> 1);
+        if (m < 8) { frag_op(1, kt, 1, m); frag_op(1, kt, 1, m + 1); }   // all reads done well before the barrier
         mfma_one(0, m + 1);
         if ((m & 3) == 2) issue_one(kt + 3, 4 + (m >> 2));     // operand B of tile kt+3
         __builtin_amdgcn_sched_barrier(0);
@@ -421,7 +432,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
           int rl = 8 * (r >> 2) + 4 * acc_rg + (r & 3);
           stage[rl * SPITCH + nj * 32 + acc_col] = acc[mi][nj][r];
         }
-      __syncthreads();
+      // the staging slab is private to this wavefront and LDS executes a wavefront's accesses
+      // in order, so no workgroup barrier is needed between the writes and the reads below
+      __builtin_amdgcn_wave_barrier();
       const int slab_row0 = row0 + wm * 128 + mi * 32;
       if (TR::DUAL) {
         // lanes: 8 per row (8 columns each), 8 rows per pass
@@ -541,8 +554,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
           }
         }
       }
-      __syncthreads();
+      __builtin_amdgcn_wave_barrier();
     }
+    __syncthreads();   // the next tile's loads land in LDS that other wavefronts used for staging
 #if defined(EXP_CYCLES)
     unsigned long long t_d = __builtin_amdgcn_s_memtime();
     c_pro += t_b - t_a; c_loop += t_c - t_b; c_epi += t_d - t_c; n_it += nk;
