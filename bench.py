@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--workload", default="dsv3-like-share")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run three plain 1 GiB device copies (a kernel of known HBM "
+                         "traffic) so that a rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the expert layer; --gpus must be 1 "
@@ -97,6 +100,14 @@ def main():
     B.moe_profile_enable(False)
     ms_per_step = elapsed * 1e3 / args.steps
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     d, f, T, k = wl.d, wl.f, wl.T, wl.k
     flop_step = C.layer_flops(R, d, f)
     value = flop_step / (ms_per_step * 1e-3) / 1e12
@@ -121,9 +132,10 @@ def main():
     roofline = None
     if bf16:
         dom = max((n for n in GEMM_FLOP_UNITS if n in kern), key=lambda n: kern[n]["avg_ms"])
-        roofline = dict(kernel=f"gg_kernel<{dom.upper()}>", bound="mfma", achieved=kern[dom]["tflops"],
+        kname = f"gg_kernel<{dom.upper()}>"
+        roofline = dict(kernel=kname, bound="mfma", achieved=kern[dom]["tflops"],
                         peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=kern[dom]["tflops"] / MFMA_BF16_PEAK_TFLOPS,
-                        traffic=None,
+                        traffic=measured_traffic(wl.name, kname),
                         all_gemms_tflops=C.layer_flops(R, d, f) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None)
     else:
         # fp32 path: plain FMA tiles on the vector ALUs
@@ -152,6 +164,18 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, logits, dy, args.cpu_seconds)
     print(json.dumps(out))
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    summary of this workload (a counter run cannot happen inside the benchmark); None if absent."""
+    path = os.path.join(ROOT, "profiles", {"dsv3-like-share": "hot_path_dsv3_hbm_traffic.md"}.get(workload, ""))
+    if not os.path.isfile(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return json.loads(line.split(":", 1)[1]).get(kernel)
+    return None
 
 
 def cpu_baseline(wl, x, logits, dy, budget_s):
