@@ -425,6 +425,21 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     const int acc_col = lane & 31, acc_rg = lane >> 5;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
+      // DA: fetch this slab's h1/h3 (all 8 passes) up front, with clamped addresses, so that
+      // their latency overlaps the staging traffic instead of serialising the passes
+      uint4 pre1[8], pre3[8];
+      if (MODE == DA) {
+#pragma unroll
+        for (int pass = 0; pass < 8; ++pass) {
+          int grow = row0 + wm * 128 + mi * 32 + pass * 4 + (lane >> 4);
+          int gcol = n0 + wn * 128 + (lane & 15) * 8;
+          if (grow > row_end - 1) grow = row_end - 1;
+          if (gcol > p.N - 8) gcol = p.N - 8;
+          const size_t idx = (size_t)grow * p.ldc + gcol;
+          pre1[pass] = *reinterpret_cast<const uint4*>(p.H1 + idx);
+          pre3[pass] = *reinterpret_cast<const uint4*>(p.H3 + idx);
+        }
+      }
 #pragma unroll
       for (int nj = 0; nj < 4; ++nj)
 #pragma unroll
@@ -509,7 +524,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
           if (grow < row_end && gcol < p.N) {
             if (MODE == DA) {
               const size_t idx = (size_t)grow * p.ldc + gcol;
-              uint4 q1 = *reinterpret_cast<const uint4*>(p.H1 + idx), q3 = *reinterpret_cast<const uint4*>(p.H3 + idx);
+              const uint4 q1 = pre1[pass], q3 = pre3[pass];
               const uint32_t* u1 = reinterpret_cast<const uint32_t*>(&q1);
               const uint32_t* u3 = reinterpret_cast<const uint32_t*>(&q3);
               float av[8], d1[8], d3[8];

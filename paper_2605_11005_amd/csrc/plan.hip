@@ -3,7 +3,7 @@
 // Three small kernels, no order-dependent atomics, so perm/inv are unique and reproducible:
 //   1. plan_hist    -- every wavefront owns CHUNK consecutive slots and writes the histogram
 //                      of their local experts to ws_hist[chunk][e].
-//   2. plan_scan    -- one block: per expert, an exclusive running sum over the chunks
+//   2. plan_scan    -- one block, one wavefront per expert: an exclusive running sum over the chunks
 //                      (-> first row of that expert inside each chunk), then the exclusive
 //                      prefix over experts (-> offsets), clamped to cap with a status word.
 //   3. plan_scatter -- every wavefront revisits its chunk in slot order; within each group
@@ -35,18 +35,27 @@ __global__ __launch_bounds__(64) void plan_hist(const int32_t* __restrict__ topk
 }
 
 // ws_hist[c][e] becomes the first row (before the expert's offset is added) of expert e in chunk c.
+// One wavefront per expert: 64 chunks at a time, exclusive scan by lane shuffles, carry across
+// groups of 64.
 __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ ws_hist, int n_chunks, int e_cnt, int cap,
                                                  int32_t* __restrict__ offsets, int32_t* __restrict__ status) {
   __shared__ int32_t total[MOE_MAX_LOCAL + 1];
-  const int e = threadIdx.x;
-  if (e < e_cnt) {
-    int run = 0;
-    for (int c = 0; c < n_chunks; ++c) {
-      int v = ws_hist[(size_t)c * e_cnt + e];
-      ws_hist[(size_t)c * e_cnt + e] = run;
-      run += v;
+  const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE, n_waves = blockDim.x / WAVE;
+  for (int e = wave; e < e_cnt; e += n_waves) {
+    int carry = 0;
+    for (int c0 = 0; c0 < n_chunks; c0 += WAVE) {
+      const int c = c0 + lane;
+      const int v = c < n_chunks ? ws_hist[(size_t)c * e_cnt + e] : 0;
+      int incl = v;
+#pragma unroll
+      for (int off = 1; off < WAVE; off <<= 1) {
+        int t = __shfl_up(incl, off, WAVE);
+        if (lane >= off) incl += t;
+      }
+      if (c < n_chunks) ws_hist[(size_t)c * e_cnt + e] = carry + incl - v;
+      carry += __shfl(incl, WAVE - 1, WAVE);
     }
-    total[e] = run;
+    if (lane == 0) total[e] = carry;
   }
   __syncthreads();
   if (threadIdx.x == 0) {

@@ -1,18 +1,18 @@
 // Row movers: dispatch (token order -> expert order) and combine (expert order -> token
-// order, gate-weighted).  Both are token-major with one wavefront per token, so every row
+// order, gate-weighted).  Both are token-major (a token's row is split over a few blocks), so every row
 // of x / o is read exactly once and every row of xp / y is written exactly once:
 //   dispatch : read x[t] once (skipped when the token has no local slot), write it to each
 //              of the token's local rows            -> (U + R) * d * b bytes
 //   combine  : read the token's local rows, write y[t] once (zeros when none)
 //                                                   -> (R + T) * d * b bytes
-// Accesses are 16 bytes per lane, whole rows per wavefront, several loads in flight.
+// Accesses are 16 bytes per lane and one vector per thread (grid = row segments x tokens):
+// on this chip a plain copy is fastest with the largest possible number of small threads.
 #include "common.h"
 #include "kernels.h"
 
 namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-constexpr int WPB = 4;   // wavefronts (tokens) per block
 
 template <bool BF16>
 __device__ __forceinline__ u32x4 scale_vec(u32x4 v, float sc) {
@@ -33,47 +33,32 @@ __device__ __forceinline__ u32x4 scale_vec(u32x4 v, float sc) {
   }
 }
 
-// row_vecs = number of 16-byte vectors per row
+// row_vecs = number of 16-byte vectors per row.  grid = (tokens, row segments of blockDim.x vectors);
+// one vector per thread: the copy is fastest with many small independent threads.
+// Block sizes are set at launch: dispatch (write-heavy) is fastest with 256-thread blocks,
+// combine (read-heavy gather) with one block per token row (up to 1024 threads).
+constexpr int DISPATCH_BLOCK = 256;
+constexpr int COMBINE_BLOCK_MAX = 1024;
+
 template <bool BF16, bool SCALED>
-__global__ __launch_bounds__(WPB * WAVE) void dispatch_rows(const u32x4* __restrict__ x, int T, int row_vecs, int k,
-                                                           const int32_t* __restrict__ inv,
-                                                           const float* __restrict__ row_scale,
-                                                           u32x4* __restrict__ xp) {
-  const int lane = lane_id();
-  const int t = blockIdx.x * WPB + threadIdx.x / WAVE;
-  if (t >= T) return;
-  int my_row = -1;
-  float my_sc = 1.0f;
-  if (lane < k) {
-    my_row = inv[(size_t)t * k + lane];
-    if (SCALED) my_sc = row_scale[(size_t)t * k + lane];
-  }
-  unsigned long long local = __ballot(my_row >= 0);
-  if (!local) return;
-  const u32x4* src = x + (size_t)t * row_vecs;
-  for (int c0 = 0; c0 < row_vecs; c0 += 4 * WAVE) {
-    u32x4 v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      int c = c0 + u * WAVE + lane;
-      if (c < row_vecs) v[u] = __builtin_nontemporal_load(src + c);
-    }
-    unsigned long long m = local;
-    while (m) {
-      const int j = __ffsll((long long)m) - 1;
-      m &= m - 1;
-      const int row = __shfl(my_row, j, WAVE);
-      const float sc = SCALED ? __shfl(my_sc, j, WAVE) : 1.0f;
-      u32x4* dst = xp + (size_t)row * row_vecs;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        int c = c0 + u * WAVE + lane;
-        if (c < row_vecs) {
-          u32x4 o = SCALED ? scale_vec<BF16>(v[u], sc) : v[u];
-          __builtin_nontemporal_store(o, dst + c);
-        }
-      }
-    }
+__global__ __launch_bounds__(DISPATCH_BLOCK) void dispatch_rows(const u32x4* __restrict__ x, int T, int row_vecs, int k,
+                                                    const int32_t* __restrict__ inv,
+                                                    const float* __restrict__ row_scale,
+                                                    u32x4* __restrict__ xp) {
+  const int t = blockIdx.x;
+  const int c = blockIdx.y * blockDim.x + threadIdx.x;
+  const int32_t* irow = inv + (size_t)t * k;         // uniform address: scalar loads
+  int first = -1;
+  for (int j = 0; j < k; ++j)
+    if (irow[j] >= 0) { first = j; break; }
+  if (first < 0 || c >= row_vecs) return;             // token without a local slot: nothing is read
+  const u32x4 v = __builtin_nontemporal_load(x + (size_t)t * row_vecs + c);
+  for (int j = first; j < k; ++j) {
+    const int row = irow[j];
+    if (row < 0) continue;
+    const float sc = SCALED ? row_scale[(size_t)t * k + j] : 1.0f;
+    const u32x4 o = SCALED ? scale_vec<BF16>(v, sc) : v;
+    __builtin_nontemporal_store(o, xp + (size_t)row * row_vecs + c);
   }
 }
 
@@ -104,52 +89,25 @@ __device__ __forceinline__ u32x4 pack_acc(const float* acc) {
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(WPB * WAVE) void combine_rows(const u32x4* __restrict__ o, int T, int row_vecs, int k,
-                                                          const int32_t* __restrict__ inv,
-                                                          const float* __restrict__ topk_w,
-                                                          u32x4* __restrict__ y) {
-  const int lane = lane_id();
-  const int t = blockIdx.x * WPB + threadIdx.x / WAVE;
-  if (t >= T) return;
-  int my_row = -1;
-  float my_w = 1.0f;
-  if (lane < k) {
-    my_row = inv[(size_t)t * k + lane];
-    if (topk_w) my_w = topk_w[(size_t)t * k + lane];
+__global__ __launch_bounds__(COMBINE_BLOCK_MAX) void combine_rows(const u32x4* __restrict__ o, int T, int row_vecs, int k,
+                                                   const int32_t* __restrict__ inv,
+                                                   const float* __restrict__ topk_w,
+                                                   u32x4* __restrict__ y) {
+  const int t = blockIdx.x;
+  const int c = blockIdx.y * blockDim.x + threadIdx.x;
+  if (c >= row_vecs) return;
+  const int32_t* irow = inv + (size_t)t * k;         // uniform address: scalar loads
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int j = 0; j < k; ++j) {                       // ascending slot j
+    const int row = irow[j];
+    if (row < 0) continue;
+    const float w = topk_w ? topk_w[(size_t)t * k + j] : 1.0f;
+    const u32x4 v = __builtin_nontemporal_load(o + (size_t)row * row_vecs + c);
+    fma_vec<BF16>(acc, v, w);
   }
-  const unsigned long long local = __ballot(my_row >= 0);
-  u32x4* dst = y + (size_t)t * row_vecs;
-  for (int c0 = 0; c0 < row_vecs; c0 += 2 * WAVE) {
-    float acc[2][8];
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[u][i] = 0.f;
-    unsigned long long m = local;
-    while (m) {                                       // ascending slot j
-      const int j = __ffsll((long long)m) - 1;
-      m &= m - 1;
-      const int row = __shfl(my_row, j, WAVE);
-      const float w = __shfl(my_w, j, WAVE);
-      const u32x4* src = o + (size_t)row * row_vecs;
-      u32x4 v[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        int c = c0 + u * WAVE + lane;
-        if (c < row_vecs) v[u] = __builtin_nontemporal_load(src + c);
-      }
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        int c = c0 + u * WAVE + lane;
-        if (c < row_vecs) fma_vec<BF16>(acc[u], v[u], w);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      int c = c0 + u * WAVE + lane;
-      if (c < row_vecs) __builtin_nontemporal_store(pack_acc<BF16>(acc[u]), dst + c);
-    }
-  }
+  __builtin_nontemporal_store(pack_acc<BF16>(acc), y + (size_t)t * row_vecs + c);
 }
 
 }  // namespace
@@ -159,7 +117,7 @@ int launch_dispatch_rows(const void* x, int dtype, int T, int d, int k, const in
   if (T == 0) return MOE_OK;
   ProfScope prof(MOE_K_DISPATCH, s);
   const int row_vecs = dtype == MOE_BF16 ? d / 8 : d / 4;
-  dim3 grid((T + WPB - 1) / WPB), block(WPB * WAVE);
+  dim3 grid(T, (row_vecs + DISPATCH_BLOCK - 1) / DISPATCH_BLOCK), block(DISPATCH_BLOCK);
   const u32x4* xs = (const u32x4*)x;
   u32x4* xd = (u32x4*)xp;
   if (dtype == MOE_BF16) {
@@ -178,7 +136,9 @@ int launch_combine_rows(const void* o, int dtype, int T, int d, int k, const int
   if (T == 0) return MOE_OK;
   ProfScope prof(MOE_K_COMBINE, s);
   const int row_vecs = dtype == MOE_BF16 ? d / 8 : d / 4;
-  dim3 grid((T + WPB - 1) / WPB), block(WPB * WAVE);
+  int bs = (row_vecs + WAVE - 1) / WAVE * WAVE;
+  if (bs > COMBINE_BLOCK_MAX) bs = COMBINE_BLOCK_MAX;
+  dim3 grid(T, (row_vecs + bs - 1) / bs), block(bs);
   if (dtype == MOE_BF16)
     hipLaunchKernelGGL((combine_rows<true>), grid, block, 0, s, (const u32x4*)o, T, row_vecs, k, inv, topk_w, (u32x4*)y);
   else

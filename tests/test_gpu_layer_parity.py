@@ -21,6 +21,9 @@ CASES = [
     W.SKEW.scaled(name="skew-small", T=6144, d=256, f=128),
     W.MIXTRAL.scaled(name="one-expert", T=700, d=128, f=128, E=1, e_cnt=1, k=1),
     W.DSV3.scaled(name="wide-tail", T=1500, d=320, f=448, E=64, e_lo=8, e_cnt=8, k=6),
+    W.QWEN.scaled(name="narrow-k", T=700, d=64, f=64),                       # two k-tiles only
+    W.DSV3.scaled(name="many-experts", T=1024, d=64, f=128, E=512, e_lo=100, e_cnt=300, k=4),
+    W.TINY.scaled(name="fp32-many-experts", T=200, d=32, f=48, E=400, e_lo=0, e_cnt=400, k=5),
 ]
 
 
