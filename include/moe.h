@@ -112,7 +112,8 @@ int moe_dispatch(const void* x, int dtype, int T, int d, int k, const int32_t* t
  *   xp [cap,d]; w1,w3 [e_cnt,d,f]; w2 [e_cnt,f,d] (local slice: index 0 = expert e_lo)
  *   h1,h3 [cap,f]  out, saved for the backward pass; both NULL = forward only
  *   o  [cap,d]     out.  Rows >= R of every output are left untouched.
- *   ws             device scratch (holds a [cap,f]), moe_workspace_bytes(MOE_WS_EXPERT_FWD,..)
+ *   ws             device scratch (holds a [cap,f] and the tile-scheduler counters),
+ *                  moe_workspace_bytes(MOE_WS_EXPERT_FWD, ...) bytes, 256-byte aligned
  * bf16 requires d % 64 == 0 and f % 64 == 0; fp32 requires d % 4 == 0 and f % 4 == 0
  * (EUNSUPPORTED otherwise).  offsets must be non-decreasing with offsets[e_cnt] <= cap.
  */
@@ -133,7 +134,8 @@ int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
  *   dxp [cap,d] out; dw1,dw3 [e_cnt,d,f], dw2 [e_cnt,f,d] out (dtype = weight dtype)
  *   accumulate    0: dw* are overwritten (an expert without rows gets zeros);
  *                 1: the new gradient is added to the existing contents.
- *   ws            device scratch (a, dH1, dH3), moe_workspace_bytes(MOE_WS_EXPERT_BWD, ...)
+ *   ws            device scratch (a, dH1, dH3 [cap,f] and the tile-scheduler counters),
+ *                 moe_workspace_bytes(MOE_WS_EXPERT_BWD, ...) bytes, 256-byte aligned
  * Same shape restrictions as the forward.
  */
 int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d_o, int dtype,

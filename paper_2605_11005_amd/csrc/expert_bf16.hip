@@ -44,7 +44,7 @@ constexpr int OPER_BYTES = 256 * BK * 2;           // 16384: one operand tile
 constexpr int STAGE_BYTES = 2 * OPER_BYTES;        // 32768
 constexpr int TILE_LDS = NSTAGE * STAGE_BYTES;     // 131072
 constexpr int SPITCH = 132;             // floats per epilogue staging row (128 + 4 pad)
-constexpr int SMEM_BYTES = TILE_LDS + 2 * (MOE_MAX_LOCAL + 1) * 4;   // + tile_start[], offs[]
+constexpr int SMEM_BYTES = TILE_LDS + 3 * (MOE_MAX_LOCAL + 1) * 4 + 16;   // + tile_start[], offs[], order[], ticket
 static_assert(4 * 32 * SPITCH * 4 <= TILE_LDS, "epilogue staging must fit in the tile ring");
 
 enum { UP = 0, DOWN = 1, DA = 2, DX = 3, WG = 4, WGD = 5 };
@@ -58,6 +58,7 @@ struct GArgs {
   long ldc, c_es;
   const bf16_t* H1; const bf16_t* H3;     // DA epilogue inputs
   const int32_t* off;
+  int32_t* sched;                         // 8 zeroed ticket counters (one per XCD)
   int e_cnt;
   int M;                                  // WG/WGD: rows of the output (d or f)
   int N;                                  // output columns (per half for dual tiles)
@@ -150,6 +151,8 @@ struct TrIssue {
   }
 };
 
+template <int V> struct IntC { static constexpr int value = V; };
+
 // Fragment addressing.  MFMA 32x32x16 operand: lane l holds row (l&31), k = 8*(l>>5) + 0..7.
 // K-contiguous tile: one 16-byte read.  byte offset of (row, k-step s) = row*64 + ((2s + (l>>5)) ^ ((row>>2)&3))*16
 // (k-step 1 is k-step 0 with bit 5 flipped: the swizzle is an XOR, not an addition)
@@ -181,6 +184,8 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   extern __shared__ __align__(16) char smem[];
   int32_t* tile_start = reinterpret_cast<int32_t*>(smem + TILE_LDS);
   int32_t* offs = tile_start + (MOE_MAX_LOCAL + 1);      // LDS copy of the row offsets
+  int32_t* order = offs + (MOE_MAX_LOCAL + 1);           // experts by descending row count
+  int32_t* next_q = order + MOE_MAX_LOCAL;               // hand-over slot of the tile scheduler
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -188,27 +193,40 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   const int wm = wave >> 1, wn = wave & 1;
   const int e_cnt = p.e_cnt;
 
+  // ---- tile list.  Experts are taken heaviest first (ties by id), so that the cheap tiles
+  // come last and even out the end of the schedule.  position -> expert in order[];
+  // tile_start[pos] = number of tiles before that position (ragged-M modes).
   const int n_tiles_n = (p.N + TR::BN_EFF - 1) / TR::BN_EFF;
   int total;
   int wg_tiles_per_e = 0, wg_mt = 0;
   for (int e = tid; e <= e_cnt; e += NT) offs[e] = p.off[e];
+  __syncthreads();
+  for (int e = tid; e < e_cnt; e += NT) {
+    const int rows = offs[e + 1] - offs[e];
+    int rank = 0;
+    for (int o = 0; o < e_cnt; ++o) {
+      const int r2 = offs[o + 1] - offs[o];
+      rank += (r2 > rows || (r2 == rows && o < e)) ? 1 : 0;
+    }
+    order[rank] = e;
+  }
   __syncthreads();
   if (TR::RAGGED_K) {
     wg_mt = (p.M + BM - 1) / BM;
     wg_tiles_per_e = wg_mt * n_tiles_n;
     total = wg_tiles_per_e * e_cnt;
   } else {
-    // tile_start[e] = number of tiles before expert e
-    for (int e = tid; e < e_cnt; e += NT) {
-      int rows = offs[e + 1] - offs[e];
-      tile_start[e] = ((rows + BM - 1) / BM) * n_tiles_n;
+    for (int pos = tid; pos < e_cnt; pos += NT) {
+      const int e = order[pos];
+      const int rows = offs[e + 1] - offs[e];
+      tile_start[pos] = ((rows + BM - 1) / BM) * n_tiles_n;
     }
     __syncthreads();
     if (tid == 0) {
       int run = 0;
-      for (int e = 0; e < e_cnt; ++e) {
-        int v = tile_start[e];
-        tile_start[e] = run;
+      for (int pos = 0; pos < e_cnt; ++pos) {
+        int v = tile_start[pos];
+        tile_start[pos] = run;
         run += v;
       }
       tile_start[e_cnt] = run;
@@ -217,12 +235,12 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     total = tile_start[e_cnt];
   }
 
-  // XCD-aware walk: workgroup b runs on XCD b%8; give each XCD a contiguous run of tiles
-  const int G = gridDim.x;
-  const bool xcd_ok = (G % 8) == 0;
-  const int b = blockIdx.x;
-  const int first = xcd_ok ? (b % 8) * (G / 8) + b / 8 : b;
-
+  // ---- dynamic, XCD-aware tile scheduler.  The list is cut into chunks of 32 consecutive
+  // tiles (an 8 x 4 block of one expert: 8 A panels and 4 B panels); chunk c belongs to XCD
+  // c mod 8 (workgroup b runs on XCD b mod 8), whose workgroups draw tiles from it in order
+  // through one atomic counter per XCD.  Ticket q of XCD x is tile 32*(8*(q/32) + x) + q%32.
+  // The ticket for the next tile is drawn while the current one is computed.  A workgroup whose
+  // queue has run dry moves on to the next XCD's queue.
   // per-lane fragment offsets inside an operand tile (k-step 0)
   int a_off[4], b_off[4];
 #pragma unroll
@@ -233,32 +251,50 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     b_off[i] = OPER_BYTES + (TR::B_TRANS ? tr_frag_off(brow, lane) : kc_frag_off(brow + (lane & 31), lane, 0));
   }
 
-#if defined(EXP_CYCLES)
-  unsigned long long t_kernel0 = __builtin_amdgcn_s_memtime(), c_loop = 0, c_epi = 0, c_pro = 0, n_it = 0, c_w_lds = 0, c_w_vm = 0, c_w_bar = 0;
-#endif
-  for (int L = first; L < total; L += G) {
-#if defined(EXP_CYCLES)
-    unsigned long long t_a = __builtin_amdgcn_s_memtime();
-#endif
+  const int G = gridDim.x;
+  const int n_queues = (G % 8) == 0 ? 8 : 1;
+  int queue = blockIdx.x % n_queues;       // the queue this workgroup currently draws from
+  int exhausted = 0;                       // queues found empty so far
+  if (tid == 0) *next_q = atomicAdd(p.sched + queue, 1);
+  __syncthreads();
+
+  while (true) {
+    const int q = __builtin_amdgcn_readfirstlane(*next_q);
+    const int L = 32 * (n_queues * (q >> 5) + queue) + (q & 31);
+    __syncthreads();                       // everyone has read the ticket before it is replaced
+    if (L >= total) {
+      // tickets only grow, so this queue is finished: help the next XCD's queue (work stealing
+      // at the tail of the schedule), stop once every queue has been seen empty
+      if (++exhausted == n_queues) break;
+      queue = (queue + 1) % n_queues;
+      if (tid == 0) *next_q = atomicAdd(p.sched + queue, 1);
+      __syncthreads();
+      continue;
+    }
+    // draw the next ticket now; it is handed over through LDS only after the k loop, so that
+    // the atomic's latency never holds up this tile
+    int my_ticket = 0;
+    if (tid == 0) my_ticket = atomicAdd(p.sched + queue, 1);
     // ---------------------------------------------------------------- decode tile
     // Within an expert, tiles are ordered in bands of 8 m-tiles, n-tile next, m-tile inside the
-    // band fastest: 32 consecutive tiles (one XCD's share of a round) then form an 8 x 4 block
-    // that shares 8 A panels and 4 B panels through that XCD's L2.
+    // band fastest: 32 consecutive tiles (one chunk) then form an 8 x 4 block that shares 8 A
+    // panels and 4 B panels through one XCD's L2.
     int e, lo, hi, mt, nt;
     {
       int li, mte;
       if (TR::RAGGED_K) {
-        e = L / wg_tiles_per_e;
-        li = L - e * wg_tiles_per_e;
+        const int pos = L / wg_tiles_per_e;
+        li = L - pos * wg_tiles_per_e;
+        e = order[pos];
         mte = wg_mt;
       } else {
-        int a = 0, c = e_cnt;                    // largest e with tile_start[e] <= L
+        int a = 0, c = e_cnt;                    // largest position with tile_start[pos] <= L
         while (c - a > 1) {
           int mid = (a + c) >> 1;
           if (tile_start[mid] <= L) a = mid; else c = mid;
         }
-        e = a;
-        li = L - tile_start[e];
+        li = L - tile_start[a];
+        e = order[a];
         mte = 0;
       }
       e = __builtin_amdgcn_readfirstlane(e);
@@ -302,9 +338,6 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     // arithmetic below is uniform; the surplus loads re-fetch the last tile into a free stage.
     auto issue_one = [&](int kt, int q) {
       if (kt > nk - 1) kt = nk - 1;
-#if defined(EXP_FIXED_K)
-      kt &= 3;
-#endif
       const uint32_t st = smem_base + (kt & (NSTAGE - 1)) * STAGE_BYTES;
       const int j = q & 3;
       if (TR::RAGGED_K) {
@@ -385,38 +418,52 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
 #pragma unroll
       for (int o = 0; o < 8; ++o) frag_op(0, 0, 0, o);
     }
-#if defined(EXP_CYCLES)
-    unsigned long long t_b = __builtin_amdgcn_s_memtime();
-#endif
-    for (int kt = 0; kt < nk; ++kt) {
-      if (TR::RAGGED_K && kt == nk - 1) mask_tail(0, kt, 0);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int m = 0; m < 16; m += 2) {
-        mfma_one(0, m);
-        if (m < 8) { frag_op(1, kt, 1, m); frag_op(1, kt, 1, m + 1); }   // all reads done well before the barrier
-        mfma_one(0, m + 1);
-        if ((m & 3) == 2) issue_one(kt + 3, 4 + (m >> 2));     // operand B of tile kt+3
+    // MV = number of 32-row MFMA blocks of this wavefront that hold valid output rows (4, 2 or
+    // 0).  A tail tile's wavefronts whose rows lie past the expert's last row skip their MFMAs
+    // and fragment reads but keep issuing their share of the loads and meeting the barriers.
+    auto k_loop = [&](auto mv_tag) {
+      constexpr int MV = decltype(mv_tag)::value;
+      // fragment read o is needed iff it feeds a live MFMA: A0, B0..B3, A1, A2, A3
+      auto live = [](int o) { return MV == 4 || (MV == 2 && o <= 5); };
+      for (int kt = 0; kt < nk; ++kt) {
+        if (TR::RAGGED_K && kt == nk - 1) mask_tail(0, kt, 0);
         __builtin_amdgcn_sched_barrier(0);
-      }
-      asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      if (TR::RAGGED_K && kt == nk - 1) mask_tail(1, kt, 1);
 #pragma unroll
-      for (int m = 0; m < 16; m += 2) {
-        mfma_one(1, m);
-        frag_op(0, kt + 1, 0, m >> 1);
-        mfma_one(1, m + 1);
-        if ((m & 3) == 2) issue_one(kt + 4, m >> 2);           // operand A of tile kt+4
+        for (int m = 0; m < 16; m += 2) {
+          if (m < 4 * MV) mfma_one(0, m);
+          if (m < 8) {                                   // all reads done well before the barrier
+            if (live(m)) frag_op(1, kt, 1, m);
+            if (live(m + 1)) frag_op(1, kt, 1, m + 1);
+          }
+          if (m < 4 * MV) mfma_one(0, m + 1);
+          if ((m & 3) == 2) issue_one(kt + 3, 4 + (m >> 2));     // operand B of tile kt+3
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
+        if (TR::RAGGED_K && kt == nk - 1) mask_tail(1, kt, 1);
+#pragma unroll
+        for (int m = 0; m < 16; m += 2) {
+          if (m < 4 * MV) mfma_one(1, m);
+          if (live(m >> 1)) frag_op(0, kt + 1, 0, m >> 1);
+          if (m < 4 * MV) mfma_one(1, m + 1);
+          if ((m & 3) == 2) issue_one(kt + 4, m >> 2);           // operand A of tile kt+4
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
+    };
+    int mv = 4;
+    if (!TR::RAGGED_K) {
+      const int rows_left = row_end - (row0 + wm * 128);
+      mv = rows_left > 64 ? 4 : (rows_left > 0 ? 2 : 0);
     }
+    if (mv == 4) k_loop(IntC<4>{});
+    else if (mv == 2) k_loop(IntC<2>{});
+    else k_loop(IntC<0>{});
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if (tid == 0) *next_q = my_ticket;
     __syncthreads();
-#if defined(EXP_CYCLES)
-    unsigned long long t_c = __builtin_amdgcn_s_memtime();
-#endif
 
     // ---------------------------------------------------------------- epilogue
     // Each wavefront stages one 32-row slab of its 128x128 tile in LDS as fp32, then walks it
@@ -572,17 +619,17 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();   // the next tile's loads land in LDS that other wavefronts used for staging
-#if defined(EXP_CYCLES)
-    unsigned long long t_d = __builtin_amdgcn_s_memtime();
-    c_pro += t_b - t_a; c_loop += t_c - t_b; c_epi += t_d - t_c; n_it += nk;
-#endif
   }
-#if defined(EXP_CYCLES)
-  if (MODE == UP && p.H1 && blockIdx.x == 3 && tid == 0) {
-    unsigned long long* dbg = (unsigned long long*)p.H1;
-    dbg[0] = __builtin_amdgcn_s_memtime() - t_kernel0; dbg[1] = c_pro; dbg[2] = c_loop; dbg[3] = c_epi; dbg[4] = n_it; dbg[5] = c_w_lds; dbg[6] = c_w_vm; dbg[7] = c_w_bar;
-  }
-#endif
+}
+
+__global__ void zero_words(int32_t* p, int n) {
+  if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
+}
+
+// ticket counters live in the 256 bytes of slack that moe_workspace_bytes adds after the
+// activation scratch; each kernel of an entry point gets its own 8 (one per XCD)
+inline int32_t* sched_area(void* ws, size_t scratch_bytes) {
+  return reinterpret_cast<int32_t*>(static_cast<char*>(ws) + ((scratch_bytes + 255) & ~(size_t)255));
 }
 
 template <int MODE>
@@ -607,21 +654,21 @@ int launch_expert_fwd_bf16(const void* xp, int cap, int d, int f, int e_cnt, con
                            const void* w1, const void* w3, const void* w2, void* h1, void* h3, void* o,
                            void* a_ws, hipStream_t s) {
   if (cap == 0 || e_cnt == 0) return MOE_OK;
+  int32_t* sched = sched_area(a_ws, (size_t)cap * f * 2);
+  hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, sched, 16);
+  HIP_CHECK_LAUNCH();
   GArgs u = {};
   u.A0 = u.A1 = (const bf16_t*)xp; u.lda = d;
   u.B0 = (const bf16_t*)w1; u.B1 = (const bf16_t*)w3; u.ldb = f; u.b_es = (long)d * f;
   u.C0 = (bf16_t*)h1; u.C1 = (bf16_t*)h3; u.C2 = (bf16_t*)a_ws; u.ldc = f;
-  u.off = offsets; u.e_cnt = e_cnt; u.N = f; u.K = d; u.save_h = (h1 && h3) ? 1 : 0;
-#if defined(EXP_CYCLES)
-  u.H1 = (const bf16_t*)((char*)a_ws + (((size_t)cap * f * 2 + 255) & ~(size_t)255));
-#endif
+  u.off = offsets; u.sched = sched; u.e_cnt = e_cnt; u.N = f; u.K = d; u.save_h = (h1 && h3) ? 1 : 0;
   int rc = launch_gg<UP>(u, s);
   if (rc) return rc;
   GArgs w = {};
   w.A0 = w.A1 = (const bf16_t*)a_ws; w.lda = f;
   w.B0 = w.B1 = (const bf16_t*)w2; w.ldb = d; w.b_es = (long)f * d;
   w.C0 = (bf16_t*)o; w.ldc = d;
-  w.off = offsets; w.e_cnt = e_cnt; w.N = d; w.K = f;
+  w.off = offsets; w.sched = sched + 8; w.e_cnt = e_cnt; w.N = d; w.K = f;
   return launch_gg<DOWN>(w, s);
 }
 
@@ -633,6 +680,9 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   bf16_t* a = (bf16_t*)ws;
   bf16_t* dh1 = a + (size_t)cap * f;
   bf16_t* dh3 = dh1 + (size_t)cap * f;
+  int32_t* sched = sched_area(ws, 3 * (size_t)cap * f * 2);
+  hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, sched, 32);
+  HIP_CHECK_LAUNCH();
   int rc;
   if (cap > 0) {
     GArgs g = {};   // dA = d_o W2^T, epilogue -> a, dH1, dH3
@@ -640,25 +690,25 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
     g.B0 = g.B1 = (const bf16_t*)w2; g.ldb = d; g.b_es = (long)f * d;
     g.C0 = a; g.C1 = dh1; g.C2 = dh3; g.ldc = f;
     g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3;
-    g.off = offsets; g.e_cnt = e_cnt; g.N = f; g.K = d;
+    g.off = offsets; g.sched = sched; g.e_cnt = e_cnt; g.N = f; g.K = d;
     if ((rc = launch_gg<DA>(g, s))) return rc;
     GArgs x = {};   // dxp = dH1 W1^T + dH3 W3^T
     x.A0 = dh1; x.A1 = dh3; x.lda = f;
     x.B0 = (const bf16_t*)w1; x.B1 = (const bf16_t*)w3; x.ldb = f; x.b_es = (long)d * f;
     x.C0 = (bf16_t*)dxp; x.ldc = d;
-    x.off = offsets; x.e_cnt = e_cnt; x.N = d; x.K = f;
+    x.off = offsets; x.sched = sched + 8; x.e_cnt = e_cnt; x.N = d; x.K = f;
     if ((rc = launch_gg<DX>(x, s))) return rc;
   }
   GArgs w = {};     // dW2 = a^T d_o
   w.A0 = w.A1 = a; w.lda = f;
   w.B0 = w.B1 = (const bf16_t*)d_o; w.ldb = d;
   w.C0 = (bf16_t*)dw2; w.ldc = d; w.c_es = (long)f * d;
-  w.off = offsets; w.e_cnt = e_cnt; w.M = f; w.N = d; w.accumulate = accumulate;
+  w.off = offsets; w.sched = sched + 16; w.e_cnt = e_cnt; w.M = f; w.N = d; w.accumulate = accumulate;
   if ((rc = launch_gg<WG>(w, s))) return rc;
   GArgs v = {};     // dW1|dW3 = xp^T [dH1|dH3]
   v.A0 = v.A1 = (const bf16_t*)xp; v.lda = d;
   v.B0 = dh1; v.B1 = dh3; v.ldb = f;
   v.C0 = (bf16_t*)dw1; v.C1 = (bf16_t*)dw3; v.ldc = f; v.c_es = (long)d * f;
-  v.off = offsets; v.e_cnt = e_cnt; v.M = d; v.N = f; v.accumulate = accumulate;
+  v.off = offsets; v.sched = sched + 24; v.e_cnt = e_cnt; v.M = d; v.N = f; v.accumulate = accumulate;
   return launch_gg<WGD>(v, s);
 }
