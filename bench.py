@@ -100,6 +100,8 @@ def main():
     B.moe_profile_enable(False)
     ms_per_step = elapsed * 1e3 / args.steps
 
+    ceilings = measured_ceilings(B, torch)
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -137,6 +139,12 @@ def main():
                         peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=kern[dom]["tflops"] / MFMA_BF16_PEAK_TFLOPS,
                         traffic=measured_traffic(wl.name, kname),
                         all_gemms_tflops=C.layer_flops(R, d, f) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None)
+        # experts with few rows are bound by reading their weights, not by MFMA: composite bound
+        comp_ms = 1e3 * C.expert_composite_bound_s(counts.tolist(), d, f, b, MFMA_BF16_PEAK_TFLOPS * 1e12,
+                                                   HBM_PEAK_GBPS * 1e9)
+        roofline["composite_bound_ms"] = comp_ms
+        roofline["all_gemms_ms"] = gemm_ms
+        roofline["all_gemms_frac_of_composite_bound"] = comp_ms / gemm_ms if gemm_ms else None
     else:
         # fp32 path: plain FMA tiles on the vector ALUs
         fl = C.layer_flops(R, d, f)
@@ -156,7 +164,7 @@ def main():
         "config": {"workload": wl.name, "T": T, "d": d, "E": wl.E, "local_experts": wl.e_cnt, "k": k, "f": f,
                    "gate_mode": wl.gate_mode, "routed_rows_R": R, "tokens_with_local_slot_U": U,
                    "rows_per_expert_min_max": [int(counts.min()), int(counts.max())]},
-        "roofline": roofline, "hbm_kernels": hbm, "kernels": kern,
+        "roofline": roofline, "hbm_kernels": hbm, "measured_ceilings": ceilings, "kernels": kern,
         "dispatch_combine_GBps": [hbm.get("dispatch", {}).get("achieved"), hbm.get("combine", {}).get("achieved")],
         "input_generation_s": gen_s,
     }
@@ -164,6 +172,34 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, logits, dy, args.cpu_seconds)
     print(json.dumps(out))
+
+
+def measured_ceilings(B, torch):
+    """What this machine sustains, measured in the same run (outside the timed region): MFMA-only bf16
+    loops with constant and with pseudo-random operands, and a plain 1 GiB device copy."""
+    sink = torch.empty(1024 * 256, dtype=torch.float32, device="cuda")
+    out = {}
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    for tag, rnd in (("mfma_bf16_constant_operands_TFLOPs", False), ("mfma_bf16_random_operands_TFLOPs", True)):
+        flop = B.moe_probe_mfma_bf16(sink, 4000, rnd)
+        t = timed(lambda: B.moe_probe_mfma_bf16(sink, 4000, rnd), 20)    # ~20 ms of sustained load
+        out[tag] = flop / t / 1e12
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    t = timed(lambda: B.moe_probe_copy(src, dst), 10)
+    out["device_copy_GBps"] = 2.0 * (1 << 30) / t / 1e9
+    return out
 
 
 def measured_traffic(workload, kernel):

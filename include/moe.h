@@ -179,6 +179,22 @@ enum { MOE_K_ROUTE = 0, MOE_K_PLAN = 1, MOE_K_DISPATCH = 2, MOE_K_COMBINE = 3, M
 int moe_profile_enable(int on);
 int moe_profile_read(int kernel, double* total_ms /* host */, int* launches /* host */);
 
+/*
+ * Measured ceilings, for benchmarks only (not part of the expert-layer path): the rates this
+ * chip sustains under its own clock and power management, to be timed by the caller with
+ * events on `stream`.
+ *   moe_probe_mfma_bf16  enqueues an MFMA-only loop (32x32x16 bf16, 4 wavefronts per CU,
+ *                        16 independent accumulators, no memory traffic), `iters` rounds of 16
+ *                        MFMAs per wavefront; operands constant or pseudo-random (the latter
+ *                        is the realistic case: switching activity lowers the sustained clock).
+ *                        sink: device scratch of >= 256*4 bytes per CU; *flop (host) receives
+ *                        the FLOP count of the launch.
+ *   moe_probe_copy       enqueues a plain device copy of `bytes` (multiple of 16) bytes.
+ */
+int moe_probe_mfma_bf16(float* sink, size_t sink_bytes, int iters, int random_operands, double* flop /* host */,
+                        moe_stream_t stream);
+int moe_probe_copy(const void* src, void* dst, size_t bytes, moe_stream_t stream);
+
 /* Static, human-readable text for an error code. */
 const char* moe_error_string(int code);
 

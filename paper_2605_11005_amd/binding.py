@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
-           "moe_profile_enable", "moe_profile_read",
+           "moe_profile_enable", "moe_profile_read", "moe_probe_mfma_bf16", "moe_probe_copy",
            "moe_workspace_bytes", "moe_error_string")
 
 
@@ -186,3 +186,22 @@ def moe_profile_read(kernel: str):
     ms, n = ctypes.c_double(0), ctypes.c_int(0)
     _check(lib.moe_profile_read(KERNEL_IDS[kernel], ctypes.byref(ms), ctypes.byref(n)), "moe_profile_read")
     return ms.value, n.value
+
+
+def moe_probe_mfma_bf16(sink, iters: int, random_operands: bool) -> float:
+    """Enqueue the MFMA-only ceiling kernel; returns the FLOP count of the launch."""
+    lib = load_library()
+    lib.moe_probe_mfma_bf16.restype = ctypes.c_int
+    lib.moe_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                        ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    flop = ctypes.c_double(0)
+    _check(lib.moe_probe_mfma_bf16(_ptr(sink), sink.numel() * sink.element_size(), int(iters), int(random_operands),
+                                   ctypes.byref(flop), _stream()), "moe_probe_mfma_bf16")
+    return flop.value
+
+
+def moe_probe_copy(src, dst):
+    lib = load_library()
+    lib.moe_probe_copy.restype = ctypes.c_int
+    lib.moe_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    _check(lib.moe_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()), "moe_probe_copy")

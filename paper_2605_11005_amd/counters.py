@@ -46,3 +46,17 @@ def dispatch_bytes(U, R, T, k, d, elem_bytes):
 def combine_bytes(R, T, k, d, elem_bytes):
     """Row mover, expert order -> token order: read R rows, write T rows, read inv and gates."""
     return (R + T) * d * elem_bytes + 8 * T * k
+
+
+def expert_composite_bound_s(rows_per_expert, d, f, elem_bytes, peak_flops, peak_bw):
+    """Lower bound on the expert forward+backward time that accounts for experts too small to be
+    compute bound: sum over experts of max(FLOP_e / peak_flops, bytes_e / peak_bw), where
+    bytes_e counts the expert's weights (read by the forward and by the backward, gradients
+    written once: 9*d*f elements) and the minimum activation traffic of its rows (6*d + 14*f
+    elements per row over the six GEMMs)."""
+    total = 0.0
+    for rows in rows_per_expert:
+        flops = 18.0 * rows * d * f
+        byts = (9.0 * d * f + rows * (6.0 * d + 14.0 * f)) * elem_bytes
+        total += max(flops / peak_flops, byts / peak_bw)
+    return total

@@ -91,6 +91,22 @@ int moe_profile_read(int kernel, double* total_ms, int* launches) {
   return MOE_OK;
 }
 
+int moe_probe_mfma_bf16(float* sink, size_t sink_bytes, int iters, int random_operands, double* flop,
+                        moe_stream_t stream) {
+  if (!sink || iters <= 0 || iters > (1 << 22)) return MOE_EINVAL;
+  const int cus = device_cu_count();
+  if (sink_bytes < (size_t)cus * 256 * sizeof(float)) return MOE_EWORKSPACE;
+  int rc = launch_probe_mfma(sink, iters, random_operands ? 1 : 0, (hipStream_t)stream);
+  if (rc == MOE_OK && flop) *flop = (double)cus * 4.0 * (double)iters * 16.0 * 32768.0;
+  return rc;
+}
+
+int moe_probe_copy(const void* src, void* dst, size_t bytes, moe_stream_t stream) {
+  if (!src || !dst || (bytes & 15) || misaligned(src, 16) || misaligned(dst, 16)) return MOE_EINVAL;
+  if (bytes / 16 / 256 >= (1ull << 31)) return MOE_EUNSUPPORTED;
+  return launch_probe_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
 const char* moe_error_string(int code) {
   switch (code) {
     case MOE_OK: return "ok";

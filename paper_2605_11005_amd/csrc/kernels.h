@@ -34,6 +34,9 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
                            const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
                            int accumulate, void* ws, hipStream_t s);
 
+int launch_probe_mfma(float* sink, int iters, int random_operands, hipStream_t s);
+int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
 int device_cu_count();
 
 // Per-kernel timing (moe_profile_*): brackets a launch with events when profiling is on.

@@ -22,3 +22,14 @@ def test_row_mover_bytes():
     assert C.dispatch_bytes(U, R, T, k, d, 2) == (U + R) * d * 2 + 4 * (R + T * k)
     assert C.combine_bytes(R, T, k, d, 2) == (R + T) * d * 2 + 8 * T * k
     assert C.dispatch_bytes(U, R, T, k, d, 2) <= 2 * R * d * 2 + 4 * (R + T * k)   # never above "rows moved"
+
+
+def test_composite_bound_limits():
+    d, f, P, BW = 7168, 2048, 2.5e15, 8e12
+    # a large expert is compute bound, a tiny one is bound by its weights, an empty one still
+    # has its gradient written (zeros) and nothing else is charged beyond the weights term
+    big = C.expert_composite_bound_s([10000], d, f, 2, P, BW)
+    assert abs(big - 18.0 * 10000 * d * f / P) < 1e-12
+    tiny = C.expert_composite_bound_s([2], d, f, 2, P, BW)
+    assert tiny > 100 * 18.0 * 2 * d * f / P and abs(tiny - (9 * d * f + 2 * (6 * d + 14 * f)) * 2 / BW) < 1e-12
+    assert C.expert_composite_bound_s([10000, 2], d, f, 2, P, BW) == big + tiny
