@@ -199,6 +199,14 @@ def measured_ceilings(B, torch):
     dst = torch.empty_like(src)
     t = timed(lambda: B.moe_probe_copy(src, dst), 10)
     out["device_copy_GBps"] = 2.0 * (1 << 30) / t / 1e9
+    del src, dst
+    # yardstick only: the vendor library's dense bf16 GEMM (torch.matmul) on one large problem of
+    # the up-projection's shape and operand layout, random operands
+    M, K, N = 65536, 7168, 4096
+    a = torch.randn((M, K), device="cuda", dtype=torch.bfloat16)
+    w = torch.randn((K, N), device="cuda", dtype=torch.bfloat16) * K ** -0.5
+    t = timed(lambda: torch.matmul(a, w), 10)
+    out["vendor_dense_gemm_bf16_TFLOPs"] = 2.0 * M * N * K / t / 1e12
     return out
 
 
