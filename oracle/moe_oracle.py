@@ -204,3 +204,65 @@ def layer_bwd(fw, dy, k, w1, w3, w2):
     dxp, dw1, dw3, dw2 = expert_bwd(fw["xp"], fw["h1"], fw["h3"], d_o, fw["offsets"], w1, w3, w2)
     dx = combine(dxp, fw["inv"], None)
     return dict(d_o=d_o, dxp=dxp, dw1=dw1, dw3=dw3, dw2=dw2, dx=dx)
+
+
+# ------------------------------------------------------------------ router (trainable gate)
+# The gate is trainable (MoE background section): logits = x Wr, and the loss gradient reaches
+# Wr and x through the gate weights.  Selection is held fixed (it is piecewise constant).
+def router_logits(x, wr):
+    """logits [T,E] = x [T,d] @ Wr [d,E], float64 accumulate, returned as the float32 the router emits."""
+    return (np.asarray(x, dtype=np.float64) @ np.asarray(wr, dtype=np.float64)).astype(np.float32)
+
+
+def gate_grad(dy, o, inv):
+    """dg[t,j] = <dy[t], o[inv[t,j]]> for local slots, 0 for slots whose expert is not local
+    (y = sum_j g[t,j] * o[inv[t,j]], so this is d<dy,y>/dg)."""
+    dy = np.asarray(dy, dtype=np.float64)
+    o = np.asarray(o, dtype=np.float64)
+    inv = np.asarray(inv)
+    T, k = inv.shape
+    dg = np.zeros((T, k))
+    for j in range(k):
+        rows = inv[:, j]
+        m = rows >= 0
+        dg[m, j] = np.einsum("td,td->t", dy[m], o[rows[m]])
+    return dg
+
+
+def gate_bwd(logits, topk_idx, dg, gate_mode):
+    """d<dy,y>/dlogits [T,E] given the complete dg [T,k], selection held fixed."""
+    l = np.asarray(logits, dtype=np.float32).astype(np.float64)
+    idx = np.asarray(topk_idx).astype(np.int64)
+    dg = np.asarray(dg, dtype=np.float64)
+    T, E = l.shape
+    dl = np.zeros((T, E))
+    sel = np.take_along_axis(l, idx, axis=1)
+    if gate_mode == GATE_SOFTMAX_RENORM:
+        w = np.exp(sel - sel.max(axis=1, keepdims=True))
+        w /= w.sum(axis=1, keepdims=True)                     # softmax over the selected logits
+        d_sel = w * (dg - (w * dg).sum(axis=1, keepdims=True))
+        np.put_along_axis(dl, idx, d_sel, axis=1)
+    elif gate_mode == GATE_SIGMOID_RENORM:
+        s = 1.0 / (1.0 + np.exp(-sel))
+        S = s.sum(axis=1, keepdims=True)
+        w = s / S
+        ds = (dg - (w * dg).sum(axis=1, keepdims=True)) / S
+        np.put_along_axis(dl, idx, ds * s * (1.0 - s), axis=1)
+    elif gate_mode == GATE_SOFTMAX:
+        p = np.exp(l - l.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        ps = np.take_along_axis(p, idx, axis=1)
+        inner = (ps * dg).sum(axis=1, keepdims=True)          # sum over selected of p_i dg_i
+        dl = -p * inner
+        np.put_along_axis(dl, idx, ps * (dg - inner), axis=1)
+    else:
+        raise ValueError("gate_mode")
+    return dl
+
+
+def router_bwd(x, wr, dlogits):
+    """dWr [d,E] = x^T dlogits;  router term of dx [T,d] = dlogits Wr^T."""
+    x = np.asarray(x, dtype=np.float64)
+    wr = np.asarray(wr, dtype=np.float64)
+    dl = np.asarray(dlogits, dtype=np.float64)
+    return x.T @ dl, dl @ wr.T
