@@ -40,7 +40,7 @@ typedef void* moe_stream_t; /* hipStream_t */
 enum { MOE_OK = 0, MOE_EINVAL = 1, MOE_EUNSUPPORTED = 2, MOE_EWORKSPACE = 3, MOE_EHIP = 4 };
 enum { MOE_F32 = 0, MOE_BF16 = 1 };
 enum { MOE_GATE_SOFTMAX_RENORM = 0, MOE_GATE_SIGMOID_RENORM = 1, MOE_GATE_SOFTMAX = 2 };
-enum { MOE_WS_DISPATCH = 0, MOE_WS_EXPERT_FWD = 1, MOE_WS_EXPERT_BWD = 2 };
+enum { MOE_WS_DISPATCH = 0, MOE_WS_EXPERT_FWD = 1, MOE_WS_EXPERT_BWD = 2, MOE_WS_ROUTER = 3 };
 
 /* Limits checked by the entry points (MOE_EUNSUPPORTED beyond them). */
 #define MOE_MAX_EXPERTS 1024 /* E */
@@ -156,8 +156,63 @@ int moe_combine(const void* o, int dtype, int T, int d, int k, const int32_t* in
                 const float* topk_w, void* y, moe_stream_t stream);
 
 /* Scratch bytes needed by the call named by `which` (MOE_WS_*) at these sizes; 0 on
- * invalid arguments is never returned for valid ones (at least 256). */
+ * invalid arguments is never returned for valid ones (at least 256).  For MOE_WS_ROUTER
+ * (moe_router_fwd and moe_router_bwd share one size) pass E in the e_cnt argument. */
 size_t moe_workspace_bytes(int which, int dtype, int T, int k, int d, int f, int e_cnt, int cap);
+
+/*
+ * The trainable gate (MoE background section: the gate network that scores the experts is
+ * trainable).  logits = x Wr, and the loss reaches Wr and x a second time through the gate
+ * weights that multiply the expert outputs.  Expert selection is held fixed in the backward
+ * pass (it is piecewise constant in the logits).  Order of the calls in a training step:
+ *   forward : moe_router_fwd -> moe_route -> moe_dispatch -> moe_expert_fwd -> moe_combine
+ *   backward: moe_combine_bwd (replaces the scaled moe_dispatch) -> moe_expert_bwd ->
+ *             moe_combine(dxp, no gate) -> moe_gate_bwd -> moe_router_bwd (adds into dx)
+ *
+ * moe_router_fwd -- logits [T,E] float = x [T,d] Wr [d,E], fp32 accumulation.
+ *   x and wr have type `dtype`; bf16 requires d % 8 == 0.  ws: moe_workspace_bytes(MOE_WS_ROUTER).
+ */
+int moe_router_fwd(const void* x, const void* wr, int dtype, int T, int d, int E, float* logits,
+                   void* ws, size_t ws_bytes, moe_stream_t stream);
+
+/*
+ * moe_combine_bwd -- backward of moe_combine with respect to both of its inputs, in one pass
+ * over dy:
+ *     d_o[inv[t,j], :] = topk_w[t,j] * dy[t, :]                    (as the scaled moe_dispatch)
+ *     dgate[t,j]       = < dy[t, :], o[inv[t,j], :] >               (0 where inv[t,j] == -1)
+ *   dy [T,d], o [rows,d], d_o [rows,d] of type dtype; inv [T,k]; topk_w, dgate [T,k] float.
+ * The dot product is accumulated in fp32 in a fixed order (reproducible run to run).  With a
+ * local expert slice dgate holds this GPU's slots only; moe_gate_bwd is linear in dgate, so
+ * partial results add across GPUs.
+ */
+int moe_combine_bwd(const void* dy, const void* o, int dtype, int T, int d, int k, const int32_t* inv,
+                    const float* topk_w, void* d_o, float* dgate, moe_stream_t stream);
+
+/*
+ * moe_gate_bwd -- gradient with respect to the logits through the gate weights, selection fixed.
+ * With g the gate weights of the k selected experts and c = sum_j g_j dgate_j:
+ *   SOFTMAX_RENORM : dlogit_j = g_j (dgate_j - c)                 on the selected experts, else 0
+ *   SIGMOID_RENORM : dlogit_j = (dgate_j - c) s_j (1 - s_j) / S   (s logistic scores, S their sum
+ *                                                                  over the selection), else 0
+ *   SOFTMAX        : dlogit_e = p_e ([e selected] dgate_e - c)    for all E (p softmax over all E)
+ *   logits [T,E] float, topk_idx [T,k], dgate [T,k] float -> dlogits [T,E] float (every entry written).
+ */
+int moe_gate_bwd(const float* logits, const int32_t* topk_idx, const float* dgate, int T, int E, int k,
+                 int gate_mode, float* dlogits, moe_stream_t stream);
+
+/*
+ * moe_router_bwd -- backward of moe_router_fwd:
+ *     dwr [d,E] (+)= x^T dlogits          dx [T,d] (+)= dlogits Wr^T
+ *   dwr, dx of type dtype; dlogits [T,E] float.  dwr_accumulate / dx_accumulate: 0 overwrite,
+ *   1 add to the existing contents (dx_accumulate = 1 adds the router term to the gradient that
+ *   the expert path left in dx).  Either output may be NULL to skip it.
+ *   bf16: dlogits is rounded to bf16 for the matrix cores when E % 32 == 0 and d % 64 == 0
+ *   (fp32 accumulation over T in fixed-size chunks, chunk sums added in fp32); other shapes
+ *   take a plain fp32 path.  ws: moe_workspace_bytes(MOE_WS_ROUTER).
+ */
+int moe_router_bwd(const void* x, const void* wr, const float* dlogits, int dtype, int T, int d, int E,
+                   void* dwr, int dwr_accumulate, void* dx, int dx_accumulate, void* ws, size_t ws_bytes,
+                   moe_stream_t stream);
 
 /*
  * Optional per-kernel timing, for benchmarks (measurement of the grouped GEMMs against the
@@ -174,7 +229,8 @@ size_t moe_workspace_bytes(int which, int dtype, int T, int k, int d, int f, int
  * Not thread-safe: enable, run and read from one host thread.
  */
 enum { MOE_K_ROUTE = 0, MOE_K_PLAN = 1, MOE_K_DISPATCH = 2, MOE_K_COMBINE = 3, MOE_K_UP = 4,
-       MOE_K_DOWN = 5, MOE_K_DA = 6, MOE_K_DX = 7, MOE_K_WG = 8, MOE_K_WGD = 9, MOE_K_COUNT = 10 };
+       MOE_K_DOWN = 5, MOE_K_DA = 6, MOE_K_DX = 7, MOE_K_WG = 8, MOE_K_WGD = 9, MOE_K_ROUTER_FWD = 10,
+       MOE_K_COMBINE_BWD = 11, MOE_K_GATE_BWD = 12, MOE_K_ROUTER_DW = 13, MOE_K_ROUTER_DX = 14, MOE_K_COUNT = 15 };
 #define MOE_PROFILE_MAX_EVENTS 8192
 int moe_profile_enable(int on);
 int moe_profile_read(int kernel, double* total_ms /* host */, int* launches /* host */);

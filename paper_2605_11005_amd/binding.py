@@ -12,12 +12,13 @@ import os
 
 MOE_F32, MOE_BF16 = 0, 1
 GATE_SOFTMAX_RENORM, GATE_SIGMOID_RENORM, GATE_SOFTMAX = 0, 1, 2
-WS_DISPATCH, WS_EXPERT_FWD, WS_EXPERT_BWD = 0, 1, 2
+WS_DISPATCH, WS_EXPERT_FWD, WS_EXPERT_BWD, WS_ROUTER = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
+           "moe_router_fwd", "moe_combine_bwd", "moe_gate_bwd", "moe_router_bwd",
            "moe_profile_enable", "moe_profile_read", "moe_probe_mfma_bf16", "moe_probe_copy",
            "moe_workspace_bytes", "moe_error_string")
 
@@ -54,6 +55,16 @@ def load_library():
                                    c_void_p, c_size_t, c_void_p]
     lib.moe_combine.restype = c_int
     lib.moe_combine.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.moe_router_fwd.restype = c_int
+    lib.moe_router_fwd.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.moe_combine_bwd.restype = c_int
+    lib.moe_combine_bwd.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                    c_void_p, c_void_p]
+    lib.moe_gate_bwd.restype = c_int
+    lib.moe_gate_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
+    lib.moe_router_bwd.restype = c_int
+    lib.moe_router_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_int, c_void_p,
+                                   c_int, c_void_p, c_size_t, c_void_p]
     lib.moe_workspace_bytes.restype = c_size_t
     lib.moe_workspace_bytes.argtypes = [c_int] * 8
     lib.moe_error_string.restype = ctypes.c_char_p
@@ -168,7 +179,52 @@ def moe_combine(o, inv, topk_w, y):
            "moe_combine")
 
 
-KERNEL_IDS = dict(route=0, plan=1, dispatch=2, combine=3, up=4, down=5, da=6, dx=7, wg=8, wgd=9)
+def moe_router_fwd(x, wr, logits, ws):
+    import torch
+    T, d = x.shape
+    E = wr.shape[1]
+    _need(x, name="x"); _need(wr, x.dtype, (d, E), "wr"); _need(logits, torch.float32, (T, E), "logits")
+    _need(ws, name="ws")
+    _check(load_library().moe_router_fwd(_ptr(x), _ptr(wr), _dtype_code(x), T, d, E, _ptr(logits), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream()), "moe_router_fwd")
+
+
+def moe_combine_bwd(dy, o, inv, topk_w, d_o, dgate):
+    import torch
+    T, k = inv.shape
+    d = dy.shape[1]
+    _need(dy, name="dy"); _need(o, dy.dtype, name="o"); _need(d_o, dy.dtype, tuple(o.shape), "d_o")
+    _need(inv, torch.int32, name="inv"); _need(topk_w, torch.float32, (T, k), "topk_w")
+    _need(dgate, torch.float32, (T, k), "dgate")
+    if o.shape[1] != d or dy.shape[0] != T:
+        raise MoeError("dy must be [T,d] and o [rows,d]")
+    _check(load_library().moe_combine_bwd(_ptr(dy), _ptr(o), _dtype_code(dy), T, d, k, _ptr(inv), _ptr(topk_w),
+                                          _ptr(d_o), _ptr(dgate), _stream()), "moe_combine_bwd")
+
+
+def moe_gate_bwd(logits, topk_idx, dgate, gate_mode, dlogits):
+    import torch
+    T, E = logits.shape
+    k = topk_idx.shape[1]
+    _need(logits, torch.float32, name="logits"); _need(topk_idx, torch.int32, (T, k), "topk_idx")
+    _need(dgate, torch.float32, (T, k), "dgate"); _need(dlogits, torch.float32, (T, E), "dlogits")
+    _check(load_library().moe_gate_bwd(_ptr(logits), _ptr(topk_idx), _ptr(dgate), T, E, k, gate_mode, _ptr(dlogits),
+                                       _stream()), "moe_gate_bwd")
+
+
+def moe_router_bwd(x, wr, dlogits, dwr, dwr_accumulate, dx, dx_accumulate, ws):
+    import torch
+    T, d = x.shape
+    E = wr.shape[1]
+    _need(x, name="x"); _need(wr, x.dtype, (d, E), "wr"); _need(dlogits, torch.float32, (T, E), "dlogits")
+    _need(dwr, x.dtype, (d, E), "dwr"); _need(dx, x.dtype, (T, d), "dx"); _need(ws, name="ws")
+    _check(load_library().moe_router_bwd(_ptr(x), _ptr(wr), _ptr(dlogits), _dtype_code(x), T, d, E, _ptr(dwr),
+                                         int(dwr_accumulate), _ptr(dx), int(dx_accumulate), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream()), "moe_router_bwd")
+
+
+KERNEL_IDS = dict(route=0, plan=1, dispatch=2, combine=3, up=4, down=5, da=6, dx=7, wg=8, wgd=9, router_fwd=10,
+                  combine_bwd=11, gate_bwd=12, router_dw=13, router_dx=14)
 
 
 def moe_profile_enable(on: bool):

@@ -127,8 +127,67 @@ size_t moe_workspace_bytes(int which, int dtype, int T, int k, int d, int f, int
       return align256((dtype == MOE_F32 ? 3 : 1) * (size_t)cap * f * esize(dtype)) + 256;
     case MOE_WS_EXPERT_BWD:   // a, dH1, dH3 [cap,f]
       return align256(3 * (size_t)cap * f * esize(dtype)) + 256;
+    case MOE_WS_ROUTER:       // e_cnt carries E
+      if (d <= 0 || e_cnt <= 0) return 256;
+      return router_ws_bytes(dtype, T, d, e_cnt);
     default: return 256;
   }
+}
+
+namespace {
+int shape_check_router(int dtype, int T, int d, int E) {
+  if (bad_dtype(dtype) || T < 0 || d <= 0 || E <= 0) return MOE_EINVAL;
+  if (E > MOE_MAX_EXPERTS) return MOE_EUNSUPPORTED;
+  if (dtype == MOE_BF16 && d % 8) return MOE_EUNSUPPORTED;
+  if ((long long)T * (d > E ? d : E) >= (1ll << 40) || T > (1 << 22)) return MOE_EUNSUPPORTED;
+  if ((long long)d * 256 >= (1ll << 31) || (long long)d * E >= (1ll << 31)) return MOE_EUNSUPPORTED;
+  return MOE_OK;
+}
+}  // namespace
+
+int moe_router_fwd(const void* x, const void* wr, int dtype, int T, int d, int E, float* logits, void* ws,
+                   size_t ws_bytes, moe_stream_t stream) {
+  int rc = shape_check_router(dtype, T, d, E);
+  if (rc) return rc;
+  if (!wr || (T > 0 && (!x || !logits))) return MOE_EINVAL;
+  if (misaligned(x, 16) || misaligned(wr, 16) || misaligned(logits, 16)) return MOE_EINVAL;
+  if (!ws || misaligned(ws, 256) || ws_bytes < router_ws_bytes(dtype, T, d, E)) return MOE_EWORKSPACE;
+  return launch_router_fwd(x, wr, dtype, T, d, E, logits, ws, (hipStream_t)stream);
+}
+
+int moe_combine_bwd(const void* dy, const void* o, int dtype, int T, int d, int k, const int32_t* inv,
+                    const float* topk_w, void* d_o, float* dgate, moe_stream_t stream) {
+  if (bad_dtype(dtype) || T < 0 || d <= 0 || k <= 0) return MOE_EINVAL;
+  if (k > MOE_MAX_TOPK) return MOE_EUNSUPPORTED;
+  if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
+  if (T > 0 && (!dy || !inv || !topk_w || !dgate)) return MOE_EINVAL;
+  if (misaligned(dy, 16) || misaligned(o, 16) || misaligned(d_o, 16)) return MOE_EINVAL;
+  return launch_combine_bwd(dy, o, dtype, T, d, k, inv, topk_w, d_o, dgate, (hipStream_t)stream);
+}
+
+int moe_gate_bwd(const float* logits, const int32_t* topk_idx, const float* dgate, int T, int E, int k,
+                 int gate_mode, float* dlogits, moe_stream_t stream) {
+  if (T < 0 || E <= 0 || k <= 0 || k > E) return MOE_EINVAL;
+  if (gate_mode != MOE_GATE_SOFTMAX_RENORM && gate_mode != MOE_GATE_SIGMOID_RENORM && gate_mode != MOE_GATE_SOFTMAX)
+    return MOE_EINVAL;
+  if (E > MOE_MAX_EXPERTS || k > MOE_MAX_TOPK) return MOE_EUNSUPPORTED;
+  if ((long long)T * E >= (1ll << 40)) return MOE_EUNSUPPORTED;
+  if (T > 0 && (!logits || !topk_idx || !dgate || !dlogits)) return MOE_EINVAL;
+  return launch_gate_bwd(logits, topk_idx, dgate, T, E, k, gate_mode, dlogits, (hipStream_t)stream);
+}
+
+int moe_router_bwd(const void* x, const void* wr, const float* dlogits, int dtype, int T, int d, int E,
+                   void* dwr, int dwr_accumulate, void* dx, int dx_accumulate, void* ws, size_t ws_bytes,
+                   moe_stream_t stream) {
+  int rc = shape_check_router(dtype, T, d, E);
+  if (rc) return rc;
+  if ((dwr_accumulate != 0 && dwr_accumulate != 1) || (dx_accumulate != 0 && dx_accumulate != 1)) return MOE_EINVAL;
+  if (!wr || (T > 0 && (!x || !dlogits))) return MOE_EINVAL;
+  if (misaligned(x, 16) || misaligned(wr, 16) || misaligned(dlogits, 16) || misaligned(dwr, 16) || misaligned(dx, 16))
+    return MOE_EINVAL;
+  if (!ws || misaligned(ws, 256) || ws_bytes < router_ws_bytes(dtype, T, d, E)) return MOE_EWORKSPACE;
+  return launch_router_bwd(x, wr, dlogits, dtype, T, d, E, dwr, dwr_accumulate, dx, dx_accumulate, ws,
+                           (hipStream_t)stream);
 }
 
 int moe_route(const float* logits, int T, int E, int k, int gate_mode, int e_lo, int e_cnt,

@@ -47,7 +47,11 @@ constexpr int SPITCH = 132;             // floats per epilogue staging row (128 
 constexpr int SMEM_BYTES = TILE_LDS + 3 * (MOE_MAX_LOCAL + 1) * 4 + 16;   // + tile_start[], offs[], order[], ticket
 static_assert(4 * 32 * SPITCH * 4 <= TILE_LDS, "epilogue staging must fit in the tile ring");
 
-enum { UP = 0, DOWN = 1, DA = 2, DX = 3, WG = 4, WGD = 5 };
+enum { UP = 0, DOWN = 1, DA = 2, DX = 3, WG = 4, WGD = 5,
+       // the trainable router reuses the same machinery on one full-height "expert":
+       RL = 6,    // logits = x Wr            ragged-M shape, B read transposed, fp32 output
+       RW = 7,    // dWr partials = x^T dl    ragged-K shape over fixed chunks of the tokens, fp32 output
+       RX = 8 };  // dx (+)= dl Wr^T          ragged-M shape, B K-contiguous, optional bf16 accumulate
 
 struct GArgs {
   const bf16_t* A0; const bf16_t* A1;     // A sources (A1: second K segment of DX)
@@ -57,7 +61,9 @@ struct GArgs {
   bf16_t* C0; bf16_t* C1; bf16_t* C2;     // outputs
   long ldc, c_es;
   const bf16_t* H1; const bf16_t* H3;     // DA epilogue inputs
-  const int32_t* off;
+  float* F0;                              // fp32 output (RL, RW)
+  const int32_t* off;                     // row offsets; NULL: segment e = [min(e*chunk, rows), min((e+1)*chunk, rows))
+  int rows, chunk;
   int32_t* sched;                         // 8 zeroed ticket counters (one per XCD)
   int e_cnt;
   int M;                                  // WG/WGD: rows of the output (d or f)
@@ -68,10 +74,10 @@ struct GArgs {
 };
 
 template <int MODE> struct Traits {
-  static constexpr bool A_TRANS = MODE == WG || MODE == WGD;
-  static constexpr bool B_TRANS = MODE == UP || MODE == DOWN || MODE == WG || MODE == WGD;
+  static constexpr bool A_TRANS = MODE == WG || MODE == WGD || MODE == RW;
+  static constexpr bool B_TRANS = MODE == UP || MODE == DOWN || MODE == WG || MODE == WGD || MODE == RL || MODE == RW;
   static constexpr bool DUAL = MODE == UP || MODE == WGD;
-  static constexpr bool RAGGED_K = MODE == WG || MODE == WGD;
+  static constexpr bool RAGGED_K = MODE == WG || MODE == WGD || MODE == RW;
   static constexpr int BN_EFF = DUAL ? BN / 2 : BN;   // output columns covered per tile
 };
 
@@ -199,7 +205,10 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   const int n_tiles_n = (p.N + TR::BN_EFF - 1) / TR::BN_EFF;
   int total;
   int wg_tiles_per_e = 0, wg_mt = 0;
-  for (int e = tid; e <= e_cnt; e += NT) offs[e] = p.off[e];
+  for (int e = tid; e <= e_cnt; e += NT) {
+    const long long cut = (long long)e * p.chunk;
+    offs[e] = p.off ? p.off[e] : (int)(cut < p.rows ? cut : p.rows);
+  }
   __syncthreads();
   for (int e = tid; e < e_cnt; e += NT) {
     const int rows = offs[e + 1] - offs[e];
@@ -598,10 +607,14 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               *reinterpret_cast<uint4*>(p.C0 + idx) = oa;
               *reinterpret_cast<uint4*>(p.C1 + idx) = o1;
               *reinterpret_cast<uint4*>(p.C2 + idx) = o3;
+            } else if (MODE == RL || MODE == RW) {
+              float* c0 = p.F0 + (MODE == RW ? (size_t)e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
+              *reinterpret_cast<float4*>(c0) = make_float4(x[0], x[1], x[2], x[3]);
+              *reinterpret_cast<float4*>(c0 + 4) = make_float4(x[4], x[5], x[6], x[7]);
             } else {
               const size_t idx = (MODE == WG ? (size_t)e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
               bf16_t* c0 = p.C0 + idx;
-              if (MODE == WG && p.accumulate) {
+              if ((MODE == WG || MODE == RX) && p.accumulate) {
                 uint4 q0 = *reinterpret_cast<const uint4*>(c0);
                 const uint32_t* u0 = reinterpret_cast<const uint32_t*>(&q0);
 #pragma unroll
@@ -642,7 +655,7 @@ int launch_gg(const GArgs& a, hipStream_t s) {
     attr_set = true;
   }
   int grid = device_cu_count();
-  ProfScope prof(MOE_K_UP + MODE, s);
+  ProfScope prof(MODE == RL ? MOE_K_ROUTER_FWD : MODE == RW ? MOE_K_ROUTER_DW : MODE == RX ? MOE_K_ROUTER_DX : MOE_K_UP + MODE, s);
   hipLaunchKernelGGL(gg_kernel<MODE>, dim3(grid), dim3(NT), SMEM_BYTES, s, a);
   HIP_CHECK_LAUNCH();
   return MOE_OK;
@@ -711,4 +724,55 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   v.C0 = (bf16_t*)dw1; v.C1 = (bf16_t*)dw3; v.ldc = f; v.c_es = (long)d * f;
   v.off = offsets; v.sched = sched + 24; v.e_cnt = e_cnt; v.M = d; v.N = f; v.accumulate = accumulate;
   return launch_gg<WGD>(v, s);
+}
+
+// ---- trainable router on the matrix cores (bf16, E % 32 == 0, d % 64 == 0) ----------------
+// ws layout: [0,256) ticket counters; then dl as bf16 [T,E]; then the fp32 chunk sums [S,d,E].
+int router_dw_splits(int T, int d, int E) {
+  const int tiles = ((d + BM - 1) / BM) * ((E + BN - 1) / BN);
+  int s = (device_cu_count() + tiles - 1) / tiles;
+  const int max_by_rows = (T + 4 * BK - 1) / (4 * BK);      // at least four k-tiles per chunk
+  if (s > max_by_rows) s = max_by_rows;
+  if (s > 32) s = 32;
+  return s < 1 ? 1 : s;
+}
+
+int launch_router_fwd_bf16(const void* x, const void* wr, int T, int d, int E, float* logits, int32_t* sched,
+                           hipStream_t s) {
+  if (T == 0) return MOE_OK;
+  hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, sched, 8);
+  HIP_CHECK_LAUNCH();
+  GArgs g = {};
+  g.A0 = g.A1 = (const bf16_t*)x; g.lda = d;
+  g.B0 = g.B1 = (const bf16_t*)wr; g.ldb = E; g.b_es = 0;
+  g.F0 = logits; g.ldc = E;
+  g.off = nullptr; g.rows = T; g.chunk = T; g.sched = sched; g.e_cnt = 1; g.N = E; g.K = d;
+  return launch_gg<RL>(g, s);
+}
+
+int launch_router_dw_bf16(const void* x, const void* dl_bf16, int T, int d, int E, float* partials, int splits,
+                          int32_t* sched, hipStream_t s) {
+  GArgs g = {};
+  g.A0 = g.A1 = (const bf16_t*)x; g.lda = d;
+  g.B0 = g.B1 = (const bf16_t*)dl_bf16; g.ldb = E;
+  g.F0 = partials; g.ldc = E; g.c_es = (long)d * E;
+  g.off = nullptr; g.rows = T; g.chunk = (((T + splits - 1) / splits + BK - 1) / BK) * BK;
+  g.sched = sched; g.e_cnt = splits; g.M = d; g.N = E;
+  return launch_gg<RW>(g, s);
+}
+
+int launch_router_dx_bf16(const void* dl_bf16, const void* wr, int T, int d, int E, void* dx, int accumulate,
+                          int32_t* sched, hipStream_t s) {
+  GArgs g = {};
+  g.A0 = g.A1 = (const bf16_t*)dl_bf16; g.lda = E;
+  g.B0 = g.B1 = (const bf16_t*)wr; g.ldb = E; g.b_es = 0;
+  g.C0 = (bf16_t*)dx; g.ldc = d;
+  g.off = nullptr; g.rows = T; g.chunk = T; g.sched = sched; g.e_cnt = 1; g.N = d; g.K = E; g.accumulate = accumulate;
+  return launch_gg<RX>(g, s);
+}
+
+int launch_zero_words(int32_t* p, int n, hipStream_t s) {
+  hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, p, n);
+  HIP_CHECK_LAUNCH();
+  return MOE_OK;
 }

@@ -34,6 +34,25 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
                            const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
                            int accumulate, void* ws, hipStream_t s);
 
+// trainable router (router.hip; the matrix-core variants live in expert_bf16.hip)
+size_t router_ws_bytes(int dtype, int T, int d, int E);
+int launch_router_fwd(const void* x, const void* wr, int dtype, int T, int d, int E, float* logits, void* ws,
+                      hipStream_t s);
+int launch_combine_bwd(const void* dy, const void* o, int dtype, int T, int d, int k, const int32_t* inv,
+                       const float* topk_w, void* d_o, float* dgate, hipStream_t s);
+int launch_gate_bwd(const float* logits, const int32_t* topk_idx, const float* dgate, int T, int E, int k,
+                    int gate_mode, float* dlogits, hipStream_t s);
+int launch_router_bwd(const void* x, const void* wr, const float* dlogits, int dtype, int T, int d, int E, void* dwr,
+                      int dwr_acc, void* dx, int dx_acc, void* ws, hipStream_t s);
+int router_dw_splits(int T, int d, int E);
+int launch_router_fwd_bf16(const void* x, const void* wr, int T, int d, int E, float* logits, int32_t* sched,
+                           hipStream_t s);
+int launch_router_dw_bf16(const void* x, const void* dl_bf16, int T, int d, int E, float* partials, int splits,
+                          int32_t* sched, hipStream_t s);
+int launch_router_dx_bf16(const void* dl_bf16, const void* wr, int T, int d, int E, void* dx, int accumulate,
+                          int32_t* sched, hipStream_t s);
+int launch_zero_words(int32_t* p, int n, hipStream_t s);
+
 int launch_probe_mfma(float* sink, int iters, int random_operands, hipStream_t s);
 int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 

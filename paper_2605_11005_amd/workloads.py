@@ -166,6 +166,12 @@ def skew_roles(wl: Workload):
     return hot, empty, cold
 
 
+def router_weights(wl: Workload) -> np.ndarray:
+    """Wr [d,E] ~ N(0,1/d) (second argument = variance), rounded like the workload's dtype: the
+    trainable gate's weight matrix."""
+    return round_like(wl, _normal(wl, "router", (wl.d, wl.E), wl.d ** -0.5))
+
+
 def router_logits(wl: Workload, x: np.ndarray | None = None) -> np.ndarray:
     """logits [T,E] fp32 (never bf16-rounded: the router output is fp32).
 

@@ -1,0 +1,128 @@
+"""GPU parity of the trainable gate (router GEMM, fused backward of combine, gradient through
+the gate weights, router backward) against the CPU oracle, through the C ABI.
+
+The router's logits are compared with the oracle's first; from there on both sides continue from
+the GPU's logits (uploaded bit for bit), so that a near-tie decided differently by two summation
+orders cannot turn into a different selection.  Each backward step is compared twice: against the
+oracle's own chain (the end-to-end tolerance of the dtype) and, for the element-wise gate step,
+against the oracle fed with the GPU's inputs (fp32 tolerance)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2605_11005_amd import binding as B
+from paper_2605_11005_amd import workloads as W
+from paper_2605_11005_amd.layer import MoeLayerBuffers, run_backward_router, run_forward_router, to_device, torch_dtype
+from tests.gpu_util import TOL, host, rel_err
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    W.TINY,                                                                         # fp32, E = 8: plain path
+    W.TINY.scaled(name="tiny-fp32-softmax", gate_mode=W.GATE_SOFTMAX, T=300, E=12, e_lo=3, e_cnt=5, k=3, d=72, f=100),
+    W.TINY.scaled(name="tiny-fp32-sigmoid", gate_mode=W.GATE_SIGMOID_RENORM, T=130, E=70, e_lo=0, e_cnt=70, k=6, d=40, f=36),
+    W.MIXTRAL.scaled(name="mixtral-small-router", T=2048, d=256, f=384),           # bf16, E = 8: plain path on bf16
+    W.QWEN.scaled(name="qwen-small-router", T=2048, d=256, f=192),                 # bf16, E = 128: matrix cores
+    W.DSV3.scaled(name="dsv3-small-router", T=4096, d=512, f=256),                 # E = 256, sigmoid gate
+    W.DSV3.scaled(name="ragged-router", T=1500, d=320, f=448, E=96, e_lo=8, e_cnt=8, k=6),      # tails in every dimension
+    W.QWEN.scaled(name="softmax-router", gate_mode=W.GATE_SOFTMAX, T=777, d=128, f=64, E=160, e_lo=32, e_cnt=64, k=4),
+]
+
+
+@pytest.mark.parametrize("wl", CASES, ids=lambda w: w.name)
+def test_trainable_gate_forward_backward(wl):
+    print(f"case {wl.name} T={wl.T} d={wl.d} f={wl.f} E={wl.E} slice=[{wl.e_lo},{wl.e_lo + wl.e_cnt}) k={wl.k} "
+          f"gate={wl.gate_mode} {wl.dtype}", flush=True)
+    tol = TOL[wl.dtype]
+    x = W.tokens(wl); wr = W.router_weights(wl); dy = W.out_grad(wl)
+    w1, w3, w2 = W.all_expert_weights(wl)
+    dt = torch_dtype(wl)
+    dev = dict(x=to_device(x, dt), wr=to_device(wr, dt), dy=to_device(dy, dt), w1=to_device(w1, dt),
+               w3=to_device(w3, dt), w2=to_device(w2, dt))
+    buf = MoeLayerBuffers(wl, cap=wl.T * min(wl.k, wl.e_cnt), router=True)
+    for name in ("logits", "dgate", "dlogits", "dwr", "d_o", "dx"):
+        getattr(buf, name).fill_(7.0)
+    run_forward_router(wl, dev, buf)
+    run_backward_router(wl, dev, buf)
+    torch.cuda.synchronize()
+    errs = {}
+    # router GEMM: both sides accumulate the same products, the oracle in float64
+    logits_ref = O.router_logits(x, wr)
+    logits = host(buf.logits).astype(np.float32)
+    errs["logits"] = rel_err(logits, logits_ref)
+    assert errs["logits"] < 1e-5, errs
+    # from here on: the GPU's logits on both sides
+    fw = O.layer_fwd(x, logits, wl.k, wl.gate_mode, wl.e_lo, wl.e_cnt, w1, w3, w2)
+    bw = O.layer_bwd(fw, dy, wl.k, w1, w3, w2)
+    R = int(fw["offsets"][-1])
+    assert (host(buf.topk_idx) == fw["topk_idx"]).all()
+    assert (host(buf.inv) == fw["inv"]).all()
+    errs["y"] = rel_err(host(buf.y), fw["y"])
+    errs["d_o"] = rel_err(host(buf.d_o[:R]), bw["d_o"])
+    dg = O.gate_grad(dy, fw["o"], fw["inv"])
+    dg_gpu = host(buf.dgate)
+    errs["dgate"] = rel_err(dg_gpu, dg)
+    assert not dg_gpu[fw["inv"] < 0].any(), "dgate of a slot without a local expert must be zero"
+    dl = O.gate_bwd(logits, fw["topk_idx"], dg, wl.gate_mode)
+    errs["dlogits"] = rel_err(host(buf.dlogits), dl)
+    # the gate step alone, fed with the GPU's own dgate: fp32 arithmetic on both sides
+    dl_iso = O.gate_bwd(logits, fw["topk_idx"], dg_gpu, wl.gate_mode)
+    errs["dlogits_iso"] = rel_err(host(buf.dlogits), dl_iso)
+    assert errs["dlogits_iso"] < 1e-5, errs
+    dwr, dx_r = O.router_bwd(x, wr, dl)
+    errs["dwr"] = rel_err(host(buf.dwr), dwr)
+    errs["dx_total"] = rel_err(host(buf.dx), bw["dx"] + dx_r)
+    # the router GEMMs alone, fed with the GPU's dlogits
+    dwr_iso, dx_r_iso = O.router_bwd(x, wr, host(buf.dlogits))
+    errs["dwr_iso"] = rel_err(host(buf.dwr), dwr_iso)
+    print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    bad = {k: v for k, v in errs.items() if not v < tol}
+    assert not bad, bad
+    assert np.abs(dx_r).max() > 0 and np.abs(dwr).max() > 0
+
+
+def test_router_bwd_overwrite_accumulate_and_skips():
+    wl = W.QWEN.scaled(name="router-acc", T=600, d=128, f=64, E=64, e_lo=0, e_cnt=64, k=4)
+    rng = np.random.default_rng(5)
+    x = W.tokens(wl); wr = W.router_weights(wl)
+    dl = rng.standard_normal((wl.T, wl.E)).astype(np.float32)
+    dt = torch.bfloat16
+    dx0 = rng.standard_normal((wl.T, wl.d)).astype(np.float32)
+    xd, wrd, dld = to_device(x, dt), to_device(wr, dt), to_device(dl, torch.float32)
+    ws = torch.empty(B.moe_workspace_bytes(B.WS_ROUTER, B.MOE_BF16, wl.T, wl.k, wl.d, wl.f, wl.E, 0), dtype=torch.uint8, device="cuda")
+    dwr_ref, dxr_ref = O.router_bwd(x, wr, dl)
+    dwr = torch.full((wl.d, wl.E), 3.0, dtype=dt, device="cuda")
+    dx = to_device(dx0, dt)
+    dx0r = host(dx)
+    B.moe_router_bwd(xd, wrd, dld, dwr, False, dx, True, ws)
+    torch.cuda.synchronize()
+    assert rel_err(host(dwr), dwr_ref) < 2e-2
+    assert rel_err(host(dx), dx0r + dxr_ref) < 2e-2
+    first = host(dwr)
+    B.moe_router_bwd(xd, wrd, dld, dwr, True, dx, False, ws)
+    torch.cuda.synchronize()
+    assert rel_err(host(dwr), 2 * first) < 1e-2
+    assert rel_err(host(dx), dxr_ref) < 2e-2
+    keep = dwr.clone()
+    B.moe_router_bwd(xd, wrd, dld, None, False, dx, False, ws)       # dWr skipped
+    torch.cuda.synchronize()
+    assert torch.equal(keep, dwr)
+
+
+def test_combine_bwd_matches_scaled_dispatch_bit_for_bit():
+    """d_o from the fused pass equals the scaled moe_dispatch exactly (same products, one rounding)."""
+    wl = W.DSV3.scaled(name="cb-vs-dispatch", T=3000, d=1024, f=64)
+    from tests.gpu_util import gpu_layer, make_inputs
+    inp = make_inputs(wl)
+    dev, buf = gpu_layer(wl, inp)
+    d_o2 = torch.full_like(buf.d_o, 5.0)
+    dgate = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
+    B.moe_combine_bwd(dev["dy"], buf.o, buf.inv, buf.topk_w, d_o2, dgate)
+    torch.cuda.synchronize()
+    R = int(buf.offsets[-1])
+    assert torch.equal(d_o2[:R], buf.d_o[:R])
+    dgate2 = torch.empty_like(dgate)
+    B.moe_combine_bwd(dev["dy"], buf.o, buf.inv, buf.topk_w, d_o2, dgate2)
+    torch.cuda.synchronize()
+    assert torch.equal(dgate, dgate2), "the reduction order is fixed: bit-identical run to run"
