@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="dsv3-like-share")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-router", action="store_true", help="skip the trainable-gate kernels (timed after the step)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB device copies (a kernel of known HBM "
@@ -100,6 +101,13 @@ def main():
     B.moe_profile_enable(False)
     ms_per_step = elapsed * 1e3 / args.steps
 
+    kern = {}
+    for name in B.KERNEL_IDS:
+        ms, n = B.moe_profile_read(name)
+        if n:
+            kern[name] = dict(avg_ms=ms / n, launches=n)
+    # enabling the profiler again starts a new log: the step's figures were read above
+    router = None if args.no_router else router_row(B, C, W, torch, wl, dev, buf, R, U, b)
     ceilings = measured_ceilings(B, torch)
 
     if args.calibration_copy:
@@ -114,11 +122,6 @@ def main():
     flop_step = C.layer_flops(R, d, f)
     value = flop_step / (ms_per_step * 1e-3) / 1e12
 
-    kern = {}
-    for name in B.KERNEL_IDS:
-        ms, n = B.moe_profile_read(name)
-        if n:
-            kern[name] = dict(avg_ms=ms / n, launches=n)
     gemm_ms = sum(kern[n]["avg_ms"] * kern[n]["launches"] for n in GEMM_FLOP_UNITS if n in kern) / args.steps
     for name, units in GEMM_FLOP_UNITS.items():
         if name in kern:
@@ -168,10 +171,57 @@ def main():
         "dispatch_combine_GBps": [hbm.get("dispatch", {}).get("achieved"), hbm.get("combine", {}).get("achieved")],
         "input_generation_s": gen_s,
     }
+    if router:
+        out["trainable_gate"] = router
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, logits, dy, args.cpu_seconds)
     print(json.dumps(out))
+
+
+def router_row(B, C, W, torch, wl, dev, buf, R, U, b, reps=10):
+    """The trainable-gate kernels at this workload, timed on their own after the step (they are
+    not part of `value`): router GEMM, fused backward of combine, gate backward, router backward."""
+    T, d, E, k = wl.T, wl.d, wl.E, wl.k
+    dt = dev["x"].dtype
+    code = B.MOE_BF16 if wl.dtype == "bf16" else B.MOE_F32
+    wr = torch.from_numpy(W.router_weights(wl)).cuda().to(dt)
+    logits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    dgate = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    dlogits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    dwr = torch.empty((d, E), dtype=dt, device="cuda")
+    ws = torch.empty(B.moe_workspace_bytes(B.WS_ROUTER, code, T, k, d, wl.f, E, 0), dtype=torch.uint8, device="cuda")
+
+    def run():
+        B.moe_router_fwd(dev["x"], wr, logits, ws)
+        B.moe_combine_bwd(dev["dy"], buf.o, buf.inv, buf.topk_w, buf.d_o, dgate)
+        B.moe_gate_bwd(dev["logits"], buf.topk_idx, dgate, wl.gate_mode, dlogits)
+        B.moe_router_bwd(dev["x"], wr, dlogits, dwr, False, buf.dx, True, ws)
+
+    for _ in range(3):
+        run()
+    torch.cuda.synchronize()
+    B.moe_profile_enable(True)
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    B.moe_profile_enable(False)
+    out = {}
+    gemm_flop = 2.0 * T * d * E
+    for name in ("router_fwd", "combine_bwd", "gate_bwd", "router_dw", "router_dx"):
+        ms, n = B.moe_profile_read(name)
+        if not n:
+            continue
+        avg = ms / n
+        out[name] = dict(avg_ms=avg)
+        if name in ("router_fwd", "router_dw", "router_dx"):
+            out[name]["tflops"] = gemm_flop / (avg * 1e-3) / 1e12
+    if "combine_bwd" in out:       # dy rows of tokens with a local slot + o rows read, d_o rows written
+        out["combine_bwd"]["GBps"] = ((U + 2 * R) * d * b + 12.0 * T * k) / (out["combine_bwd"]["avg_ms"] * 1e-3) / 1e9
+    if "router_dx" in out:         # dx read and written, dlogits and Wr read
+        out["router_dx"]["GBps"] = (2.0 * T * d * b + T * E * 2 + d * E * b) / (out["router_dx"]["avg_ms"] * 1e-3) / 1e9
+    out["total_ms"] = sum(v["avg_ms"] for v in out.values())
+    return out
 
 
 def measured_ceilings(B, torch):
