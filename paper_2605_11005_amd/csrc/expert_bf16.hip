@@ -43,9 +43,15 @@ constexpr int NSTAGE = 4;
 constexpr int OPER_BYTES = 256 * BK * 2;           // 16384: one operand tile
 constexpr int STAGE_BYTES = 2 * OPER_BYTES;        // 32768
 constexpr int TILE_LDS = NSTAGE * STAGE_BYTES;     // 131072
-constexpr int SPITCH = 132;             // floats per epilogue staging row (128 + 4 pad)
-constexpr int SMEM_BYTES = TILE_LDS + 3 * (MOE_MAX_LOCAL + 1) * 4 + 16;   // + tile_start[], offs[], order[], ticket
-static_assert(4 * 32 * SPITCH * 4 <= TILE_LDS, "epilogue staging must fit in the tile ring");
+// Epilogue staging, outside the tile ring: one private slab per wavefront, fp32.
+//   single-output tiles: 16 rows x 64 columns, pitch 68 floats; dual tiles: 8 rows x 128 columns, pitch 132
+constexpr int SPITCH = 68, DPITCH = 132;
+constexpr int STAGING_WAVE_BYTES = 16 * SPITCH * 4;   // 4352 >= 8 * DPITCH * 4 = 4224
+static_assert(8 * DPITCH * 4 <= STAGING_WAVE_BYTES, "dual slab must fit");
+constexpr int SCHED_OFF = TILE_LDS;                                              // tile_start[], offs[], order[], ticket
+constexpr int STAGING_OFF = (SCHED_OFF + 3 * (MOE_MAX_LOCAL + 1) * 4 + 16 + 15) & ~15;
+constexpr int SMEM_BYTES = STAGING_OFF + 4 * STAGING_WAVE_BYTES;
+static_assert(SMEM_BYTES <= 160 * 1024, "one workgroup per CU: 160 KB of LDS");
 
 enum { UP = 0, DOWN = 1, DA = 2, DX = 3, WG = 4, WGD = 5,
        // the trainable router reuses the same machinery on one full-height "expert":
@@ -264,31 +270,70 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   const int n_queues = (G % 8) == 0 ? 8 : 1;
   int queue = blockIdx.x % n_queues;       // the queue this workgroup currently draws from
   int exhausted = 0;                       // queues found empty so far
-  if (tid == 0) *next_q = atomicAdd(p.sched + queue, 1);
-  __syncthreads();
+  const uint32_t smem_base = lds_addr(smem);
 
-  while (true) {
-    const int q = __builtin_amdgcn_readfirstlane(*next_q);
-    const int L = 32 * (n_queues * (q >> 5) + queue) + (q & 31);
-    __syncthreads();                       // everyone has read the ticket before it is replaced
-    if (L >= total) {
+  // ---- state of the tile whose k loop runs next (written by next_tile)
+  int e = 0, lo = 0, hi = 0, n0 = 0;
+  int nk0 = 0, nk = 0;    // k-tiles in segment 0 / in total
+  int row0 = 0;           // first output row (global row for ragged-M, i for the weight gradients)
+  int row_end = 0;        // one past the last valid output row
+  KcIssue ia_kc, ib_kc;
+  TrIssue ia_tr, ib_tr;
+
+  // One of the 8 loads (q = 0..3: operand A, 4..7: operand B) of k-tile kt.  kt is clamped to
+  // the last tile, so every iteration issues the same number of loads and the vmcnt
+  // arithmetic below is uniform; the surplus loads re-fetch the last tile into a free stage.
+  auto issue_one = [&](int kt, int q) {
+    if (kt > nk - 1) kt = nk - 1;
+    const uint32_t st = smem_base + (kt & (NSTAGE - 1)) * STAGE_BYTES;
+    const int j = q & 3;
+    if (TR::RAGGED_K) {
+      const long k0 = (long)lo + kt * BK;
+      const int k_last_rel = hi - 1 - lo - kt * BK;
+      if (q < 4) ia_tr.template issue1<true>(j, st, wave, lane, k0, k_last_rel);
+      else ib_tr.template issue1<true>(j, st + OPER_BYTES, wave, lane, k0, k_last_rel);
+    } else {
+      const bool seg1 = MODE == DX && kt >= nk0;
+      const int k0 = (seg1 ? kt - nk0 : kt) * BK;
+      if (q < 4) ia_kc.issue1(j, st, wave, k0 + (seg1 ? p.A1 - p.A0 : 0));
+      else if (TR::B_TRANS) ib_tr.template issue1<false>(j, st + OPER_BYTES, wave, lane, k0, 0);
+      else ib_kc.issue1(j, st + OPER_BYTES, wave, k0 + (seg1 ? p.B1 - p.B0 : 0));
+    }
+  };
+  auto issue_tile = [&](int kt) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue_one(kt, q);
+  };
+
+  // ---- dynamic, XCD-aware tile scheduler.  The list is cut into chunks of 32 consecutive
+  // tiles (an 8 x 4 block of one expert: 8 A panels and 4 B panels); chunk c belongs to XCD
+  // c mod 8 (workgroup b runs on XCD b mod 8), whose workgroups draw tiles from it in order
+  // through one atomic counter per XCD.  Ticket q of XCD x is tile 32*(8*(q/32) + x) + q%32.
+  // The ticket for the tile after the next is drawn while the current one is computed.  A
+  // workgroup whose queue has run dry moves on to the next XCD's queue.
+  //
+  // next_tile: takes the ticket waiting in *next_q, decodes it into the tile state above and
+  // starts the loads of that tile's first k-tiles.  The tile ring must be free when it is
+  // called (it is called after the barrier that ends a k loop, before that tile's epilogue,
+  // so the first operands of the next tile travel while the finished one is being stored).
+  auto next_tile = [&]() -> bool {
+    int L;
+    while (true) {
+      const int q = __builtin_amdgcn_readfirstlane(*next_q);
+      L = 32 * (n_queues * (q >> 5) + queue) + (q & 31);
+      __syncthreads();                       // everyone has read the ticket before it is replaced
+      if (L < total) break;
       // tickets only grow, so this queue is finished: help the next XCD's queue (work stealing
       // at the tail of the schedule), stop once every queue has been seen empty
-      if (++exhausted == n_queues) break;
+      if (++exhausted == n_queues) return false;
       queue = (queue + 1) % n_queues;
       if (tid == 0) *next_q = atomicAdd(p.sched + queue, 1);
       __syncthreads();
-      continue;
     }
-    // draw the next ticket now; it is handed over through LDS only after the k loop, so that
-    // the atomic's latency never holds up this tile
-    int my_ticket = 0;
-    if (tid == 0) my_ticket = atomicAdd(p.sched + queue, 1);
-    // ---------------------------------------------------------------- decode tile
     // Within an expert, tiles are ordered in bands of 8 m-tiles, n-tile next, m-tile inside the
     // band fastest: 32 consecutive tiles (one chunk) then form an 8 x 4 block that shares 8 A
     // panels and 4 B panels through one XCD's L2.
-    int e, lo, hi, mt, nt;
+    int mt, nt;
     {
       int li, mte;
       if (TR::RAGGED_K) {
@@ -316,13 +361,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       nt = in_band / band_rows;
       mt = band * 8 + (in_band - nt * band_rows);
     }
-    const int n0 = nt * TR::BN_EFF;
-
-    int nk0, nk;            // k-tiles in segment 0 / in total
-    int row0;               // first output row (global row for ragged-M, i for WG)
-    int row_end;            // one past the last valid output row
-    KcIssue ia_kc, ib_kc;
-    TrIssue ia_tr, ib_tr;
+    n0 = nt * TR::BN_EFF;
     if (TR::RAGGED_K) {
       row0 = mt * BM;
       row_end = p.M;
@@ -338,34 +377,23 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       if (TR::B_TRANS) ib_tr.setup(p.B0 + (size_t)e * p.b_es, p.B1 + (size_t)e * p.b_es, TR::DUAL, p.ldb, n0, p.N, wave, lane);
       else ib_kc.setup(p.B0 + (size_t)e * p.b_es + (size_t)n0 * p.ldb, p.ldb, p.N - n0, wave, lane);
     }
-
-    // Issue the loads of k-tile kt (clamped to the last one, so that every iteration issues
-    // the same number of loads and the vmcnt arithmetic below is uniform) into its stage.
-    const uint32_t smem_base = lds_addr(smem);
-    // One of the 8 loads (q = 0..3: operand A, 4..7: operand B) of k-tile kt.  kt is clamped to
-    // the last tile, so every iteration issues the same number of loads and the vmcnt
-    // arithmetic below is uniform; the surplus loads re-fetch the last tile into a free stage.
-    auto issue_one = [&](int kt, int q) {
-      if (kt > nk - 1) kt = nk - 1;
-      const uint32_t st = smem_base + (kt & (NSTAGE - 1)) * STAGE_BYTES;
-      const int j = q & 3;
-      if (TR::RAGGED_K) {
-        const long k0 = (long)lo + kt * BK;
-        const int k_last_rel = hi - 1 - lo - kt * BK;
-        if (q < 4) ia_tr.template issue1<true>(j, st, wave, lane, k0, k_last_rel);
-        else ib_tr.template issue1<true>(j, st + OPER_BYTES, wave, lane, k0, k_last_rel);
-      } else {
-        const bool seg1 = MODE == DX && kt >= nk0;
-        const int k0 = (seg1 ? kt - nk0 : kt) * BK;
-        if (q < 4) ia_kc.issue1(j, st, wave, k0 + (seg1 ? p.A1 - p.A0 : 0));
-        else if (TR::B_TRANS) ib_tr.template issue1<false>(j, st + OPER_BYTES, wave, lane, k0, 0);
-        else ib_kc.issue1(j, st + OPER_BYTES, wave, k0 + (seg1 ? p.B1 - p.B0 : 0));
-      }
-    };
-    auto issue_tile = [&](int kt) {
+    if (nk > 0) {
+      issue_tile(0); issue_tile(1); issue_tile(2);
 #pragma unroll
-      for (int q = 0; q < 8; ++q) issue_one(kt, q);
-    };
+      for (int q = 0; q < 4; ++q) issue_one(3, q);
+    }
+    return true;
+  };
+
+  if (tid == 0) *next_q = atomicAdd(p.sched + queue, 1);
+  __syncthreads();
+  bool have = next_tile();
+
+  while (have) {
+    // draw the ticket of the tile after this one now; it is handed over through LDS only
+    // after the k loop, so that the atomic's latency never holds up a tile
+    int my_ticket = 0;
+    if (tid == 0) my_ticket = atomicAdd(p.sched + queue, 1);
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -418,11 +446,11 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     // The instruction order inside an iteration is fixed by hand (scheduling fences after every
     // MFMA pair): 16 MFMAs of k-step 0 with the 8 fragment reads of k-step 1 between them,
     // barrier, 16 MFMAs of k-step 1 with the next tile's first fragment reads between them.
+    // The first 28 loads (k-tiles 0..2 and operand A of k-tile 3) were issued by next_tile; the
+    // stores of the previous tile's epilogue were issued after them and share the counter, so
+    // the first wait is for everything.
     if (nk > 0) {
-      issue_tile(0); issue_tile(1); issue_tile(2);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) issue_one(3, q);
-      asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
 #pragma unroll
       for (int o = 0; o < 8; ++o) frag_op(0, 0, 0, o);
@@ -474,125 +502,149 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     if (tid == 0) *next_q = my_ticket;
     __syncthreads();
 
+    // the ring is free: decode the next tile and start its first loads, then store this one
+    const int ep_e = e, ep_row0 = row0, ep_row_end = row_end, ep_n0 = n0;
+    have = next_tile();
+
     // ---------------------------------------------------------------- epilogue
-    // Each wavefront stages one 32-row slab of its 128x128 tile in LDS as fp32, then walks it
-    // row-major so that global accesses are 16 bytes per lane and contiguous along rows.
-    float* stage = reinterpret_cast<float*>(smem) + wave * (32 * SPITCH);
+    // Each wavefront moves its 128x128 accumulators through a private LDS slab (outside the
+    // tile ring, which already receives the next tile), 16 slabs per tile, and walks each slab
+    // row-major so that global accesses are 16 bytes per lane and 128 bytes per row segment.
+    // A slab is private to its wavefront and LDS executes a wavefront's accesses in order, so
+    // no workgroup barrier is needed between the writes and the reads.
+    float* stage = reinterpret_cast<float*>(smem + STAGING_OFF) + wave * (STAGING_WAVE_BYTES / 4);
     const int acc_col = lane & 31, acc_rg = lane >> 5;
+    if (TR::DUAL) {
+      // slab = 8 rows x 128 columns: both halves of a dual tile, so that a lane holds h1 and h3
+      // (or dW1 and dW3) of the same position.  lanes: 8 per row (8 columns each).
+      const int c8 = lane & 7, rl = lane >> 3;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-      // DA: fetch this slab's h1/h3 (all 8 passes) up front, with clamped addresses, so that
-      // their latency overlaps the staging traffic instead of serialising the passes
-      uint4 pre1[8], pre3[8];
-      if (MODE == DA) {
+      for (int sl = 0; sl < 16; ++sl) {
+        const int mi = sl >> 2, g = sl & 3;
 #pragma unroll
-        for (int pass = 0; pass < 8; ++pass) {
-          int grow = row0 + wm * 128 + mi * 32 + pass * 4 + (lane >> 4);
-          int gcol = n0 + wn * 128 + (lane & 15) * 8;
-          if (grow > row_end - 1) grow = row_end - 1;
-          if (gcol > p.N - 8) gcol = p.N - 8;
-          const size_t idx = (size_t)grow * p.ldc + gcol;
-          pre1[pass] = *reinterpret_cast<const uint4*>(p.H1 + idx);
-          pre3[pass] = *reinterpret_cast<const uint4*>(p.H3 + idx);
-        }
-      }
+        for (int nj = 0; nj < 4; ++nj)
 #pragma unroll
-      for (int nj = 0; nj < 4; ++nj)
+          for (int i = 0; i < 4; ++i) stage[(4 * acc_rg + i) * DPITCH + nj * 32 + acc_col] = acc[mi][nj][4 * g + i];
+        __builtin_amdgcn_wave_barrier();
+        const int grow = ep_row0 + wm * 128 + mi * 32 + 8 * g + rl;
+        const int gcol = ep_n0 + wn * 64 + c8 * 8;
+        const float* s1 = stage + rl * DPITCH + c8 * 8;
+        const float* s3 = s1 + 64;
+        float x1[8], x3[8];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int rl = 8 * (r >> 2) + 4 * acc_rg + (r & 3);
-          stage[rl * SPITCH + nj * 32 + acc_col] = acc[mi][nj][r];
-        }
-      // the staging slab is private to this wavefront and LDS executes a wavefront's accesses
-      // in order, so no workgroup barrier is needed between the writes and the reads below
-      __builtin_amdgcn_wave_barrier();
-      const int slab_row0 = row0 + wm * 128 + mi * 32;
-      if (TR::DUAL) {
-        // lanes: 8 per row (8 columns each), 8 rows per pass
-        const int c8 = lane & 7;
+        for (int i = 0; i < 8; ++i) { x1[i] = s1[i]; x3[i] = s3[i]; }
+        __builtin_amdgcn_wave_barrier();
+        if (grow < ep_row_end && gcol < p.N) {
+          if (MODE == UP) {
+            const size_t idx = (size_t)grow * p.ldc + gcol;
+            uint4 o1, o3, oa;
+            uint32_t* w1 = reinterpret_cast<uint32_t*>(&o1);
+            uint32_t* w3 = reinterpret_cast<uint32_t*>(&o3);
+            uint32_t* wa = reinterpret_cast<uint32_t*>(&oa);
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-          const int rl = pass * 8 + (lane >> 3);
-          const int grow = slab_row0 + rl;
-          const int gcol = n0 + wn * 64 + c8 * 8;
-          const float* s1 = stage + rl * SPITCH + c8 * 8;
-          const float* s3 = s1 + 64;
-          float x1[8], x3[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) { x1[i] = s1[i]; x3[i] = s3[i]; }
-          if (grow < row_end && gcol < p.N) {
-            if (MODE == UP) {
-              const size_t idx = (size_t)grow * p.ldc + gcol;
-              uint4 o1, o3, oa;
-              uint32_t* w1 = reinterpret_cast<uint32_t*>(&o1);
-              uint32_t* w3 = reinterpret_cast<uint32_t*>(&o3);
-              uint32_t* wa = reinterpret_cast<uint32_t*>(&oa);
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                w1[i] = pack_bf16x2(x1[2 * i], x1[2 * i + 1]);
-                w3[i] = pack_bf16x2(x3[2 * i], x3[2 * i + 1]);
-                wa[i] = pack_bf16x2(silu_f(x1[2 * i]) * x3[2 * i], silu_f(x1[2 * i + 1]) * x3[2 * i + 1]);
-              }
-              if (p.save_h) {
-                *reinterpret_cast<uint4*>(p.C0 + idx) = o1;
-                *reinterpret_cast<uint4*>(p.C1 + idx) = o3;
-              }
-              *reinterpret_cast<uint4*>(p.C2 + idx) = oa;
-            } else {   // WGD: two weight-gradient outputs
-              const size_t idx = (size_t)e * p.c_es + (size_t)grow * p.ldc + gcol;
-              bf16_t* c0 = p.C0 + idx;
-              bf16_t* c1 = p.C1 + idx;
-              if (p.accumulate) {
-                uint4 q0 = *reinterpret_cast<const uint4*>(c0), q1 = *reinterpret_cast<const uint4*>(c1);
-                const uint32_t* u0 = reinterpret_cast<const uint32_t*>(&q0);
-                const uint32_t* u1 = reinterpret_cast<const uint32_t*>(&q1);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                  x1[2 * i] += bf16lo(u0[i]); x1[2 * i + 1] += bf16hi(u0[i]);
-                  x3[2 * i] += bf16lo(u1[i]); x3[2 * i + 1] += bf16hi(u1[i]);
-                }
-              }
-              uint4 o1, o3;
-              uint32_t* w1 = reinterpret_cast<uint32_t*>(&o1);
-              uint32_t* w3 = reinterpret_cast<uint32_t*>(&o3);
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                w1[i] = pack_bf16x2(x1[2 * i], x1[2 * i + 1]);
-                w3[i] = pack_bf16x2(x3[2 * i], x3[2 * i + 1]);
-              }
-              *reinterpret_cast<uint4*>(c0) = o1;
-              *reinterpret_cast<uint4*>(c1) = o3;
+            for (int i = 0; i < 4; ++i) {
+              w1[i] = pack_bf16x2(x1[2 * i], x1[2 * i + 1]);
+              w3[i] = pack_bf16x2(x3[2 * i], x3[2 * i + 1]);
+              wa[i] = pack_bf16x2(silu_f(x1[2 * i]) * x3[2 * i], silu_f(x1[2 * i + 1]) * x3[2 * i + 1]);
             }
+            if (p.save_h) {
+              *reinterpret_cast<uint4*>(p.C0 + idx) = o1;
+              *reinterpret_cast<uint4*>(p.C1 + idx) = o3;
+            }
+            *reinterpret_cast<uint4*>(p.C2 + idx) = oa;
+          } else {   // WGD: two weight-gradient outputs
+            const size_t idx = (size_t)ep_e * p.c_es + (size_t)grow * p.ldc + gcol;
+            bf16_t* c0 = p.C0 + idx;
+            bf16_t* c1 = p.C1 + idx;
+            if (p.accumulate) {
+              uint4 q0 = *reinterpret_cast<const uint4*>(c0), q1 = *reinterpret_cast<const uint4*>(c1);
+              const uint32_t* u0 = reinterpret_cast<const uint32_t*>(&q0);
+              const uint32_t* u1 = reinterpret_cast<const uint32_t*>(&q1);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                x1[2 * i] += bf16lo(u0[i]); x1[2 * i + 1] += bf16hi(u0[i]);
+                x3[2 * i] += bf16lo(u1[i]); x3[2 * i + 1] += bf16hi(u1[i]);
+              }
+            }
+            uint4 o1, o3;
+            uint32_t* w1 = reinterpret_cast<uint32_t*>(&o1);
+            uint32_t* w3 = reinterpret_cast<uint32_t*>(&o3);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              w1[i] = pack_bf16x2(x1[2 * i], x1[2 * i + 1]);
+              w3[i] = pack_bf16x2(x3[2 * i], x3[2 * i + 1]);
+            }
+            *reinterpret_cast<uint4*>(c0) = o1;
+            *reinterpret_cast<uint4*>(c1) = o3;
           }
         }
-      } else {
-        // lanes: 16 per row (8 columns each), 4 rows per pass
-        const int c8 = lane & 15;
+      }
+    } else {
+      // slab = 16 rows x 64 columns; lanes: 8 per row (8 columns each), 8 rows per pass.
+      // slab sl: accumulator block row mi = sl/4, row half h = (sl/2)%2, column pair np = sl%2.
+      const int c8 = lane & 7;
+      // DA: h1/h3 of a slab are fetched DA_AHEAD slabs before they are needed (clamped
+      // addresses), so that their latency is hidden behind the slabs in between
+      constexpr int DA_AHEAD = 3;
+      uint4 pre1[DA_AHEAD + 1][2], pre3[DA_AHEAD + 1][2];
+      auto da_fetch = [&](int sl) {
+        const int mi = sl >> 2, h = (sl >> 1) & 1, np = sl & 1;
 #pragma unroll
-        for (int pass = 0; pass < 8; ++pass) {
-          const int rl = pass * 4 + (lane >> 4);
-          const int grow = slab_row0 + rl;
-          const int gcol = n0 + wn * 128 + c8 * 8;
-          const float* sp = stage + rl * SPITCH + c8 * 8;
-          float x[8];
+        for (int pass = 0; pass < 2; ++pass) {
+          int grow = ep_row0 + wm * 128 + mi * 32 + 16 * h + pass * 8 + (lane >> 3);
+          int gcol = ep_n0 + wn * 128 + np * 64 + c8 * 8;
+          if (grow > ep_row_end - 1) grow = ep_row_end - 1;
+          if (gcol > p.N - 8) gcol = p.N - 8;
+          const size_t idx = (size_t)grow * p.ldc + gcol;
+          pre1[sl % (DA_AHEAD + 1)][pass] = *reinterpret_cast<const uint4*>(p.H1 + idx);
+          pre3[sl % (DA_AHEAD + 1)][pass] = *reinterpret_cast<const uint4*>(p.H3 + idx);
+        }
+      };
+      if (MODE == DA) {
 #pragma unroll
-          for (int i = 0; i < 8; ++i) x[i] = sp[i];
-          if (grow < row_end && gcol < p.N) {
+        for (int sl = 0; sl < DA_AHEAD; ++sl) da_fetch(sl);
+      }
+#pragma unroll
+      for (int sl = 0; sl < 16; ++sl) {
+        const int mi = sl >> 2, h = (sl >> 1) & 1, np = sl & 1;
+        if (MODE == DA && sl + DA_AHEAD < 16) da_fetch(sl + DA_AHEAD);
+#pragma unroll
+        for (int gg = 0; gg < 2; ++gg)
+#pragma unroll
+          for (int nn = 0; nn < 2; ++nn)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              stage[(8 * gg + 4 * acc_rg + i) * SPITCH + nn * 32 + acc_col] = acc[mi][2 * np + nn][4 * (2 * h + gg) + i];
+        __builtin_amdgcn_wave_barrier();
+        float xs[2][8];
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+          const float* sp = stage + (pass * 8 + (lane >> 3)) * SPITCH + c8 * 8;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) xs[pass][i] = sp[i];
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+          const int grow = ep_row0 + wm * 128 + mi * 32 + 16 * h + pass * 8 + (lane >> 3);
+          const int gcol = ep_n0 + wn * 128 + np * 64 + c8 * 8;
+          float* x = xs[pass];
+          if (grow < ep_row_end && gcol < p.N) {
             if (MODE == DA) {
               const size_t idx = (size_t)grow * p.ldc + gcol;
-              const uint4 q1 = pre1[pass], q3 = pre3[pass];
+              const uint4 q1 = pre1[sl % (DA_AHEAD + 1)][pass], q3 = pre3[sl % (DA_AHEAD + 1)][pass];
               const uint32_t* u1 = reinterpret_cast<const uint32_t*>(&q1);
               const uint32_t* u3 = reinterpret_cast<const uint32_t*>(&q3);
               float av[8], d1[8], d3[8];
 #pragma unroll
               for (int i = 0; i < 8; ++i) {
                 float z = (i & 1) ? bf16hi(u1[i >> 1]) : bf16lo(u1[i >> 1]);
-                float g = (i & 1) ? bf16hi(u3[i >> 1]) : bf16lo(u3[i >> 1]);
+                float gv = (i & 1) ? bf16hi(u3[i >> 1]) : bf16lo(u3[i >> 1]);
                 float ds;
-                float sl = silu_grad_f(z, &ds);
-                av[i] = sl * g;
-                d1[i] = x[i] * g * ds;
-                d3[i] = x[i] * sl;
+                float sl_ = silu_grad_f(z, &ds);
+                av[i] = sl_ * gv;
+                d1[i] = x[i] * gv * ds;
+                d3[i] = x[i] * sl_;
               }
               uint4 oa, o1, o3;
               uint32_t* wa = reinterpret_cast<uint32_t*>(&oa);
@@ -608,11 +660,11 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               *reinterpret_cast<uint4*>(p.C1 + idx) = o1;
               *reinterpret_cast<uint4*>(p.C2 + idx) = o3;
             } else if (MODE == RL || MODE == RW) {
-              float* c0 = p.F0 + (MODE == RW ? (size_t)e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
+              float* c0 = p.F0 + (MODE == RW ? (size_t)ep_e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
               *reinterpret_cast<float4*>(c0) = make_float4(x[0], x[1], x[2], x[3]);
               *reinterpret_cast<float4*>(c0 + 4) = make_float4(x[4], x[5], x[6], x[7]);
             } else {
-              const size_t idx = (MODE == WG ? (size_t)e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
+              const size_t idx = (MODE == WG ? (size_t)ep_e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
               bf16_t* c0 = p.C0 + idx;
               if ((MODE == WG || MODE == RX) && p.accumulate) {
                 uint4 q0 = *reinterpret_cast<const uint4*>(c0);
@@ -629,9 +681,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
           }
         }
       }
-      __builtin_amdgcn_wave_barrier();
     }
-    __syncthreads();   // the next tile's loads land in LDS that other wavefronts used for staging
   }
 }
 
