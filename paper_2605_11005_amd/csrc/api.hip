@@ -119,14 +119,13 @@ const char* moe_error_string(int code) {
 }
 
 size_t moe_workspace_bytes(int which, int dtype, int T, int k, int d, int f, int e_cnt, int cap) {
-  (void)d;
   if (T < 0 || k < 0 || f < 0 || e_cnt < 0 || cap < 0) return 256;
   switch (which) {
     case MOE_WS_DISPATCH: return align256(plan_ws_bytes(T, k, e_cnt));
     case MOE_WS_EXPERT_FWD:   // a [cap,f] (+ h1, h3 when the caller does not keep them, fp32 path)
       return align256((dtype == MOE_F32 ? 3 : 1) * (size_t)cap * f * esize(dtype)) + 256;
-    case MOE_WS_EXPERT_BWD:   // a, dH1, dH3 [cap,f]
-      return align256(3 * (size_t)cap * f * esize(dtype)) + 256;
+    case MOE_WS_EXPERT_BWD:   // a, dH1, dH3 [cap,f]; bf16 adds scheduler words and the weight-gradient partial tiles
+      return align256(3 * (size_t)cap * f * esize(dtype)) + (dtype == MOE_BF16 && d > 0 ? expert_bwd_extra_ws_bytes(d, f) : 256);
     case MOE_WS_ROUTER:       // e_cnt carries E
       if (d <= 0 || e_cnt <= 0) return 256;
       return router_ws_bytes(dtype, T, d, e_cnt);

@@ -48,8 +48,9 @@ constexpr int TILE_LDS = NSTAGE * STAGE_BYTES;     // 131072
 constexpr int SPITCH = 68, DPITCH = 132;
 constexpr int STAGING_WAVE_BYTES = 16 * SPITCH * 4;   // 4352 >= 8 * DPITCH * 4 = 4224
 static_assert(8 * DPITCH * 4 <= STAGING_WAVE_BYTES, "dual slab must fit");
-constexpr int SCHED_OFF = TILE_LDS;                                              // tile_start[], offs[], order[], ticket
-constexpr int STAGING_OFF = (SCHED_OFF + 3 * (MOE_MAX_LOCAL + 1) * 4 + 16 + 15) & ~15;
+// scheduler tables after the ring: tile_start[L+1], offs[L+1], split[L] (int32), order[L] (uint16), ticket
+constexpr int SCHED_BYTES = 2 * (MOE_MAX_LOCAL + 1) * 4 + MOE_MAX_LOCAL * 4 + MOE_MAX_LOCAL * 2 + 16;
+constexpr int STAGING_OFF = (TILE_LDS + SCHED_BYTES + 15) & ~15;
 constexpr int SMEM_BYTES = STAGING_OFF + 4 * STAGING_WAVE_BYTES;
 static_assert(SMEM_BYTES <= 160 * 1024, "one workgroup per CU: 160 KB of LDS");
 
@@ -70,6 +71,14 @@ struct GArgs {
   float* F0;                              // fp32 output (RL, RW)
   const int32_t* off;                     // row offsets; NULL: segment e = [min(e*chunk, rows), min((e+1)*chunk, rows))
   int rows, chunk;
+  // Weight gradients of experts with far more rows than the average are cut along the rows into
+  // up to split_budget pieces in total, whose fp32 partial tiles go to P0 (piece s at
+  // P0 + s * p_stride; the second output of a dual tile at + M*N) and are added up, in piece
+  // order, by wgrad_reduce.  plan[e] = (first piece << 8) | pieces  (pieces == 1: not cut).
+  float* P0;
+  long p_stride;
+  int split_budget;
+  int32_t* plan;
   int32_t* sched;                         // 8 zeroed ticket counters (one per XCD)
   int e_cnt;
   int M;                                  // WG/WGD: rows of the output (d or f)
@@ -196,8 +205,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   extern __shared__ __align__(16) char smem[];
   int32_t* tile_start = reinterpret_cast<int32_t*>(smem + TILE_LDS);
   int32_t* offs = tile_start + (MOE_MAX_LOCAL + 1);      // LDS copy of the row offsets
-  int32_t* order = offs + (MOE_MAX_LOCAL + 1);           // experts by descending row count
-  int32_t* next_q = order + MOE_MAX_LOCAL;               // hand-over slot of the tile scheduler
+  int32_t* split = offs + (MOE_MAX_LOCAL + 1);           // ragged-K modes: (first piece << 8) | pieces, by expert
+  uint16_t* order = reinterpret_cast<uint16_t*>(split + MOE_MAX_LOCAL);   // experts by descending row count
+  int32_t* next_q = reinterpret_cast<int32_t*>(order + MOE_MAX_LOCAL);    // hand-over slot of the tile scheduler
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -223,13 +233,68 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       const int r2 = offs[o + 1] - offs[o];
       rank += (r2 > rows || (r2 == rows && o < e)) ? 1 : 0;
     }
-    order[rank] = e;
+    order[rank] = (uint16_t)e;
   }
   __syncthreads();
   if (TR::RAGGED_K) {
+    // Every expert has the same number of output tiles, but a tile's cost is the expert's row
+    // count.  An expert whose k loop is longer than a workgroup's fair share of the whole launch
+    // (in k-tiles) bounds the kernel from below; it is cut into pieces of about half that share
+    // (at least 16 k-tiles) when the time saved exceeds the time to write and re-read the fp32
+    // partial tiles (p_stride floats per piece, priced at ~4 TB/s against ~0.85 us per k-tile),
+    // heaviest experts first while the budget of partial tiles lasts.
     wg_mt = (p.M + BM - 1) / BM;
     wg_tiles_per_e = wg_mt * n_tiles_n;
-    total = wg_tiles_per_e * e_cnt;
+    if (tid == 0) {
+      long long units = 0;
+      for (int e = 0; e < e_cnt; ++e) units += (offs[e + 1] - offs[e] + BK - 1) / BK;
+      const int share = (int)(units * wg_tiles_per_e / gridDim.x);
+      const int target = share / 2 > 16 ? share / 2 : 16;
+      const int piece_cost = (int)(p.p_stride / 400000) + 1;
+      int used = 0;
+      for (int pos = 0; pos < e_cnt; ++pos) {
+        const int e = order[pos];
+        const int nke = (offs[e + 1] - offs[e] + BK - 1) / BK;
+        int pieces = 1;
+        if (nke > share) {
+          pieces = (nke + target - 1) / target;
+          if (pieces > 255) pieces = 255;
+          if (pieces > p.split_budget - used) pieces = p.split_budget - used;
+          if (pieces < 2 || nke - share <= pieces * piece_cost) pieces = 1;
+        }
+        if (pieces > 1) used += pieces;
+        split[e] = pieces;
+      }
+    }
+    __syncthreads();
+    // list the experts again, now by the length of one tile's k loop (a cut expert's pieces are
+    // shorter than the tiles of the next heaviest ones), longest first
+    for (int e = tid; e < e_cnt; e += NT) {
+      const int len = ((offs[e + 1] - offs[e] + BK - 1) / BK + split[e] - 1) / split[e];
+      int rank = 0;
+      for (int o = 0; o < e_cnt; ++o) {
+        const int l2 = ((offs[o + 1] - offs[o] + BK - 1) / BK + split[o] - 1) / split[o];
+        rank += (l2 > len || (l2 == len && o < e)) ? 1 : 0;
+      }
+      order[rank] = (uint16_t)e;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int run = 0, used = 0;
+      for (int pos = 0; pos < e_cnt; ++pos) {
+        const int e = order[pos];
+        const int pieces = split[e];
+        split[e] = pieces > 1 ? ((used << 8) | pieces) : 1;
+        if (pieces > 1) used += pieces;
+        tile_start[pos] = run;
+        run += pieces * wg_tiles_per_e;
+      }
+      tile_start[e_cnt] = run;
+    }
+    __syncthreads();
+    total = tile_start[e_cnt];
+    if (p.plan && blockIdx.x == 0)
+      for (int e = tid; e < e_cnt; e += NT) p.plan[e] = split[e];
   } else {
     for (int pos = tid; pos < e_cnt; pos += NT) {
       const int e = order[pos];
@@ -274,6 +339,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
 
   // ---- state of the tile whose k loop runs next (written by next_tile)
   int e = 0, lo = 0, hi = 0, n0 = 0;
+  int piece = -1;         // ragged-K modes: index of the fp32 partial tile to write, or -1
   int nk0 = 0, nk = 0;    // k-tiles in segment 0 / in total
   int row0 = 0;           // first output row (global row for ragged-M, i for the weight gradients)
   int row_end = 0;        // one past the last valid output row
@@ -336,25 +402,32 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     int mt, nt;
     {
       int li, mte;
-      if (TR::RAGGED_K) {
-        const int pos = L / wg_tiles_per_e;
-        li = L - pos * wg_tiles_per_e;
-        e = order[pos];
-        mte = wg_mt;
-      } else {
-        int a = 0, c = e_cnt;                    // largest position with tile_start[pos] <= L
-        while (c - a > 1) {
-          int mid = (a + c) >> 1;
-          if (tile_start[mid] <= L) a = mid; else c = mid;
-        }
-        li = L - tile_start[a];
-        e = order[a];
-        mte = 0;
+      int a = 0, c = e_cnt;                      // largest position with tile_start[pos] <= L
+      while (c - a > 1) {
+        int mid = (a + c) >> 1;
+        if (tile_start[mid] <= L) a = mid; else c = mid;
       }
-      e = __builtin_amdgcn_readfirstlane(e);
+      li = __builtin_amdgcn_readfirstlane(L - tile_start[a]);
+      e = __builtin_amdgcn_readfirstlane((int)order[a]);
       lo = __builtin_amdgcn_readfirstlane(offs[e]);
       hi = __builtin_amdgcn_readfirstlane(offs[e + 1]);
-      if (!TR::RAGGED_K) mte = (hi - lo + BM - 1) / BM;
+      if (TR::RAGGED_K) {
+        mte = wg_mt;
+        const int sp = __builtin_amdgcn_readfirstlane(split[e]);
+        const int pieces = sp & 255;
+        piece = -1;
+        if (pieces > 1) {                        // this tile covers one piece of the expert's rows
+          const int c_idx = li / wg_tiles_per_e;
+          li -= c_idx * wg_tiles_per_e;
+          const int nke = (hi - lo + BK - 1) / BK;
+          const int piece_rows = ((nke + pieces - 1) / pieces) * BK;
+          lo = __builtin_amdgcn_readfirstlane(min(hi, lo + c_idx * piece_rows));
+          hi = __builtin_amdgcn_readfirstlane(min(hi, lo + piece_rows));
+          piece = (sp >> 8) + c_idx;
+        }
+      } else {
+        mte = (hi - lo + BM - 1) / BM;
+      }
       const int band = li / (8 * n_tiles_n);
       const int in_band = li - band * 8 * n_tiles_n;
       const int band_rows = min(8, mte - band * 8);
@@ -390,10 +463,14 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   bool have = next_tile();
 
   while (have) {
-    // draw the ticket of the tile after this one now; it is handed over through LDS only
-    // after the k loop, so that the atomic's latency never holds up a tile
+    // The ticket of the tile after this one is drawn eight k-tiles before the end of the k loop
+    // (at its start if it is shorter): late, so that a workgroup commits to its next tile only
+    // when it is about to be free -- tiles are listed heaviest first and long ones must go to
+    // whoever finishes first -- yet early enough that the atomic's latency is never waited for.
+    // It is handed over through LDS after the k loop.
     int my_ticket = 0;
-    if (tid == 0) my_ticket = atomicAdd(p.sched + queue, 1);
+    const int kt_draw = nk > 8 ? nk - 8 : 0;
+    if (nk == 0 && tid == 0) my_ticket = atomicAdd(p.sched + queue, 1);
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -463,6 +540,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       // fragment read o is needed iff it feeds a live MFMA: A0, B0..B3, A1, A2, A3
       auto live = [](int o) { return MV == 4 || (MV == 2 && o <= 5); };
       for (int kt = 0; kt < nk; ++kt) {
+        if (kt == kt_draw && tid == 0) my_ticket = atomicAdd(p.sched + queue, 1);
         if (TR::RAGGED_K && kt == nk - 1) mask_tail(0, kt, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -503,7 +581,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     __syncthreads();
 
     // the ring is free: decode the next tile and start its first loads, then store this one
-    const int ep_e = e, ep_row0 = row0, ep_row_end = row_end, ep_n0 = n0;
+    const int ep_e = e, ep_row0 = row0, ep_row_end = row_end, ep_n0 = n0, ep_piece = piece;
     have = next_tile();
 
     // ---------------------------------------------------------------- epilogue
@@ -512,6 +590,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     // row-major so that global accesses are 16 bytes per lane and 128 bytes per row segment.
     // A slab is private to its wavefront and LDS executes a wavefront's accesses in order, so
     // no workgroup barrier is needed between the writes and the reads.
+    // (two instances: a piece of a cut expert stores fp32 partial tiles, every other tile the final result)
+    auto epilogue = [&](auto partial_tag) {
+    constexpr bool PARTIAL = decltype(partial_tag)::value != 0;
     float* stage = reinterpret_cast<float*>(smem + STAGING_OFF) + wave * (STAGING_WAVE_BYTES / 4);
     const int acc_col = lane & 31, acc_rg = lane >> 5;
     if (TR::DUAL) {
@@ -552,6 +633,13 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               *reinterpret_cast<uint4*>(p.C1 + idx) = o3;
             }
             *reinterpret_cast<uint4*>(p.C2 + idx) = oa;
+          } else if (PARTIAL) {   // WGD, one piece of a cut expert: fp32 partial tiles
+            float* c0 = p.P0 + (size_t)ep_piece * p.p_stride + (size_t)grow * p.ldc + gcol;
+            float* c1 = c0 + (size_t)p.M * p.N;
+            *reinterpret_cast<float4*>(c0) = make_float4(x1[0], x1[1], x1[2], x1[3]);
+            *reinterpret_cast<float4*>(c0 + 4) = make_float4(x1[4], x1[5], x1[6], x1[7]);
+            *reinterpret_cast<float4*>(c1) = make_float4(x3[0], x3[1], x3[2], x3[3]);
+            *reinterpret_cast<float4*>(c1 + 4) = make_float4(x3[4], x3[5], x3[6], x3[7]);
           } else {   // WGD: two weight-gradient outputs
             const size_t idx = (size_t)ep_e * p.c_es + (size_t)grow * p.ldc + gcol;
             bf16_t* c0 = p.C0 + idx;
@@ -659,6 +747,10 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               *reinterpret_cast<uint4*>(p.C0 + idx) = oa;
               *reinterpret_cast<uint4*>(p.C1 + idx) = o1;
               *reinterpret_cast<uint4*>(p.C2 + idx) = o3;
+            } else if (MODE == WG && PARTIAL) {   // one piece of a cut expert: fp32 partial tile
+              float* c0 = p.P0 + (size_t)ep_piece * p.p_stride + (size_t)grow * p.ldc + gcol;
+              *reinterpret_cast<float4*>(c0) = make_float4(x[0], x[1], x[2], x[3]);
+              *reinterpret_cast<float4*>(c0 + 4) = make_float4(x[4], x[5], x[6], x[7]);
             } else if (MODE == RL || MODE == RW) {
               float* c0 = p.F0 + (MODE == RW ? (size_t)ep_e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
               *reinterpret_cast<float4*>(c0) = make_float4(x[0], x[1], x[2], x[3]);
@@ -682,6 +774,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
         }
       }
     }
+    };
+    if ((MODE == WG || MODE == WGD) && ep_piece >= 0) epilogue(IntC<1>{});
+    else epilogue(IntC<0>{});
   }
 }
 
@@ -689,11 +784,71 @@ __global__ void zero_words(int32_t* p, int n) {
   if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
 }
 
+// Adds up the fp32 partial tiles of the experts that the weight-gradient kernel cut into pieces
+// (plan[e] = (first piece << 8) | pieces), in piece order, and writes the bf16 gradient.
+// Every block first lists the cut experts, then the grid walks the elements of all of them
+// together (n_out outputs of mn elements each per expert), so that a single hot expert is
+// reduced by the whole chip; with no cut expert every block exits after reading the plan.
+__global__ __launch_bounds__(256) void wgrad_reduce(const int32_t* __restrict__ plan, int e_cnt,
+                                                   const float* __restrict__ P0, long p_stride, long mn, int n_out,
+                                                   bf16_t* __restrict__ C0, bf16_t* __restrict__ C1, long c_es,
+                                                   int accumulate) {
+  __shared__ int32_t list[MOE_MAX_LOCAL];   // the cut experts in ascending order: the same list in every block
+  __shared__ uint8_t cut[MOE_MAX_LOCAL];
+  __shared__ int n_cut;
+  if (threadIdx.x == 0) n_cut = 0;
+  for (int e = threadIdx.x; e < e_cnt; e += 256) cut[e] = (plan[e] & 255) > 1;
+  __syncthreads();
+  for (int e = threadIdx.x; e < e_cnt; e += 256)
+    if (cut[e]) {
+      int rank = 0;
+      for (int j = 0; j < e; ++j) rank += cut[j];
+      list[rank] = e;
+      atomicAdd(&n_cut, 1);
+    }
+  __syncthreads();
+  const long vecs = mn / 8;                       // mn is a multiple of 64 * 64
+  const long per_e = vecs * n_out;
+  const long total = per_e * n_cut;
+  for (long g = (long)blockIdx.x * 256 + threadIdx.x; g < total; g += (long)gridDim.x * 256) {
+    const int e = list[g / per_e];
+    const long r = g % per_e;
+    const int o = (int)(r / vecs);
+    const long v = r - o * vecs;
+    const int sp = plan[e];
+    const int pieces = sp & 255;
+    const float* base = P0 + (size_t)(sp >> 8) * p_stride + (size_t)o * mn + v * 8;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int c = 0; c < pieces; ++c) {
+      const float* q = base + (size_t)c * p_stride;
+      const float4 a = *reinterpret_cast<const float4*>(q), b = *reinterpret_cast<const float4*>(q + 4);
+      acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+      acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+    }
+    uint4* dst = reinterpret_cast<uint4*>((o ? C1 : C0) + (size_t)e * c_es + v * 8);
+    if (accumulate) {
+      const uint4 q0 = *dst;
+      const uint32_t* u0 = reinterpret_cast<const uint32_t*>(&q0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { acc[2 * i] += bf16lo(u0[i]); acc[2 * i + 1] += bf16hi(u0[i]); }
+    }
+    uint4 out;
+    uint32_t* w = reinterpret_cast<uint32_t*>(&out);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(acc[2 * i], acc[2 * i + 1]);
+    *dst = out;
+  }
+}
+
 // ticket counters live in the 256 bytes of slack that moe_workspace_bytes adds after the
 // activation scratch; each kernel of an entry point gets its own 8 (one per XCD)
 inline int32_t* sched_area(void* ws, size_t scratch_bytes) {
   return reinterpret_cast<int32_t*>(static_cast<char*>(ws) + ((scratch_bytes + 255) & ~(size_t)255));
 }
+
+constexpr size_t WGRAD_PLAN_BYTES = 2 * MOE_MAX_LOCAL * 4;
 
 template <int MODE>
 int launch_gg(const GArgs& a, hipStream_t s) {
@@ -744,6 +899,10 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   bf16_t* dh1 = a + (size_t)cap * f;
   bf16_t* dh3 = dh1 + (size_t)cap * f;
   int32_t* sched = sched_area(ws, 3 * (size_t)cap * f * 2);
+  int32_t* plans = sched + 64;                                   // two plans of MOE_MAX_LOCAL words
+  float* partials = reinterpret_cast<float*>(reinterpret_cast<char*>(sched) + 256 + WGRAD_PLAN_BYTES);
+  const size_t split_bytes = wgrad_split_bytes(d, f);
+  const long mn = (long)d * f;
   hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, sched, 32);
   HIP_CHECK_LAUNCH();
   int rc;
@@ -767,13 +926,23 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   w.B0 = w.B1 = (const bf16_t*)d_o; w.ldb = d;
   w.C0 = (bf16_t*)dw2; w.ldc = d; w.c_es = (long)f * d;
   w.off = offsets; w.sched = sched + 16; w.e_cnt = e_cnt; w.M = f; w.N = d; w.accumulate = accumulate;
+  w.P0 = partials; w.p_stride = mn; w.split_budget = (int)(split_bytes / (mn * 4)); w.plan = plans;
   if ((rc = launch_gg<WG>(w, s))) return rc;
+  const int red_grid = 4 * device_cu_count();
+  hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans, e_cnt, partials, mn, mn, 1, (bf16_t*)dw2,
+                     (bf16_t*)dw2, mn, accumulate);
+  HIP_CHECK_LAUNCH();
   GArgs v = {};     // dW1|dW3 = xp^T [dH1|dH3]
   v.A0 = v.A1 = (const bf16_t*)xp; v.lda = d;
   v.B0 = dh1; v.B1 = dh3; v.ldb = f;
   v.C0 = (bf16_t*)dw1; v.C1 = (bf16_t*)dw3; v.ldc = f; v.c_es = (long)d * f;
   v.off = offsets; v.sched = sched + 24; v.e_cnt = e_cnt; v.M = d; v.N = f; v.accumulate = accumulate;
-  return launch_gg<WGD>(v, s);
+  v.P0 = partials; v.p_stride = 2 * mn; v.split_budget = (int)(split_bytes / (2 * mn * 4)); v.plan = plans + MOE_MAX_LOCAL;
+  if ((rc = launch_gg<WGD>(v, s))) return rc;
+  hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans + MOE_MAX_LOCAL, e_cnt, partials, 2 * mn, mn, 2,
+                     (bf16_t*)dw1, (bf16_t*)dw3, mn, accumulate);
+  HIP_CHECK_LAUNCH();
+  return MOE_OK;
 }
 
 // ---- trainable router on the matrix cores (bf16, E % 32 == 0, d % 64 == 0) ----------------
@@ -826,3 +995,14 @@ int launch_zero_words(int32_t* p, int n, hipStream_t s) {
   HIP_CHECK_LAUNCH();
   return MOE_OK;
 }
+
+// fp32 partial tiles for weight gradients cut along the rows: room for up to 32 pieces of the
+// larger (two-output) gradient, at most 512 MB
+size_t wgrad_split_bytes(int d, int f) {
+  const size_t piece = 2 * (size_t)d * f * 4;
+  size_t b = 32 * piece;
+  const size_t cap = (size_t)512 << 20;
+  if (b > cap) b = cap / piece * piece;
+  return b;
+}
+size_t expert_bwd_extra_ws_bytes(int d, int f) { return 256 + WGRAD_PLAN_BYTES + wgrad_split_bytes(d, f); }

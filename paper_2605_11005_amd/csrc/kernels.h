@@ -53,6 +53,10 @@ int launch_router_dx_bf16(const void* dl_bf16, const void* wr, int T, int d, int
                           int32_t* sched, hipStream_t s);
 int launch_zero_words(int32_t* p, int n, hipStream_t s);
 
+// bytes that launch_expert_bwd_bf16 uses after the three [cap,f] activation buffers
+size_t expert_bwd_extra_ws_bytes(int d, int f);
+size_t wgrad_split_bytes(int d, int f);
+
 int launch_probe_mfma(float* sink, int iters, int random_operands, hipStream_t s);
 int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 

@@ -73,7 +73,18 @@ SKEW = Workload("dsv3-skew", 5, T=32768, d=7168, E=256, e_lo=0, e_cnt=32, k=8, f
                 dtype="bf16", gate_mode=GATE_SIGMOID_RENORM, routing="skew")
 
 CONFIGS = [TINY, MIXTRAL, QWEN, DSV3, SKEW]
-BY_NAME = {w.name: w for w in CONFIGS}
+
+# The three models of the paper's model-configuration table (hidden size, experts, top-k, expert
+# hidden size) as one GPU's share under 8-way expert parallelism, 16384 tokens per step.
+# Hidden sizes 2880 and 1408 are not multiples of the 256-wide GEMM tile: N and M tail tiles.
+DSMOE_T2 = Workload("deepseek-moe-share", 6, T=16384, d=2048, E=64, e_lo=0, e_cnt=8, k=4, f=1408,
+                    dtype="bf16", gate_mode=GATE_SOFTMAX_RENORM, routing="zipf", zipf_s=1.0)
+GPTOSS_T2 = Workload("gpt-oss-share", 7, T=16384, d=2880, E=128, e_lo=0, e_cnt=16, k=4, f=2880,
+                     dtype="bf16", gate_mode=GATE_SOFTMAX_RENORM, routing="zipf", zipf_s=1.0)
+QWEN3_T2 = Workload("qwen3-share", 8, T=16384, d=4096, E=128, e_lo=0, e_cnt=16, k=8, f=1536,
+                    dtype="bf16", gate_mode=GATE_SOFTMAX_RENORM, routing="zipf", zipf_s=1.0)
+MODEL_TABLE = [DSMOE_T2, GPTOSS_T2, QWEN3_T2]
+BY_NAME = {w.name: w for w in CONFIGS + MODEL_TABLE}
 
 
 # ----------------------------------------------------------------------------- bf16

@@ -21,7 +21,7 @@ from tests.gpu_util import TOL, host, rel_err
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("wl", [W.MIXTRAL, W.QWEN, W.DSV3, W.SKEW], ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", [W.MIXTRAL, W.QWEN, W.DSV3, W.SKEW] + W.MODEL_TABLE, ids=lambda w: w.name)
 def test_full_size_layer(wl):
     t0 = time.time()
     print(f"full-size case {wl.name}: T={wl.T} d={wl.d} f={wl.f} E={wl.E} local={wl.e_cnt} k={wl.k}", flush=True)

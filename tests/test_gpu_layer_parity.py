@@ -24,6 +24,13 @@ CASES = [
     W.QWEN.scaled(name="narrow-k", T=700, d=64, f=64),                       # two k-tiles only
     W.DSV3.scaled(name="many-experts", T=1024, d=64, f=128, E=512, e_lo=100, e_cnt=300, k=4),
     W.TINY.scaled(name="fp32-many-experts", T=200, d=32, f=48, E=400, e_lo=0, e_cnt=400, k=5),
+    # one expert with far more rows than a workgroup's share: its weight gradients are cut along the rows
+    W.MIXTRAL.scaled(name="one-hot-expert", T=5000, d=128, f=192, E=1, e_cnt=1, k=1),
+    W.QWEN.scaled(name="hot-and-cold", T=4096, d=320, f=192, E=24, e_lo=0, e_cnt=24, k=2, zipf_s=2.5),
+    # the paper's model table at its real hidden sizes (tail tiles in N and M), few tokens and experts
+    W.DSMOE_T2.scaled(name="deepseek-moe-small", T=1024, E=16, e_cnt=3),
+    W.GPTOSS_T2.scaled(name="gpt-oss-small", T=640, E=16, e_cnt=2),
+    W.QWEN3_T2.scaled(name="qwen3-small", T=512, E=32, e_cnt=3),
 ]
 
 
@@ -38,7 +45,7 @@ def test_layer_forward_backward(wl):
 
 
 def test_accumulate_adds_to_existing_gradients():
-    wl = W.QWEN.scaled(name="qwen-acc", T=1024, d=128, f=128)
+    wl = W.QWEN.scaled(name="qwen-acc", T=4096, d=128, f=128, zipf_s=2.0)      # includes experts cut along the rows
     inp = make_inputs(wl)
     fw, bw = oracle_layer(wl, inp)
     dev, buf = gpu_layer(wl, inp)
