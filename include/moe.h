@@ -134,8 +134,11 @@ int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
  *   dxp [cap,d] out; dw1,dw3 [e_cnt,d,f], dw2 [e_cnt,f,d] out (dtype = weight dtype)
  *   accumulate    0: dw* are overwritten (an expert without rows gets zeros);
  *                 1: the new gradient is added to the existing contents.
- *   ws            device scratch (a, dH1, dH3 [cap,f] and the tile-scheduler counters),
- *                 moe_workspace_bytes(MOE_WS_EXPERT_BWD, ...) bytes, 256-byte aligned
+ *   ws            device scratch (a, dH1, dH3 [cap,f], the tile-scheduler counters and, for bf16,
+ *                 fp32 partial tiles for the weight gradients of experts with far more rows than
+ *                 the others, which are accumulated in pieces -- at most 512 MB),
+ *                 moe_workspace_bytes(MOE_WS_EXPERT_BWD, ...) bytes, 256-byte aligned.
+ * Results are bit-reproducible from run to run (every sum has a fixed order).
  * Same shape restrictions as the forward.
  */
 int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d_o, int dtype,
