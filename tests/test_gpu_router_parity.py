@@ -126,3 +126,62 @@ def test_combine_bwd_matches_scaled_dispatch_bit_for_bit():
     B.moe_combine_bwd(dev["dy"], buf.o, buf.inv, buf.topk_w, d_o2, dgate2)
     torch.cuda.synchronize()
     assert torch.equal(dgate, dgate2), "the reduction order is fixed: bit-identical run to run"
+
+
+def test_trainable_gate_full_size_sampled():
+    """The gate kernels at the DeepSeek-V3-like share, in the launch configuration bench.py times.
+    Compared on what the oracle can compute one by one: logits of sampled tokens, dgate of sampled
+    tokens (from the GPU's own o rows), dlogits in full (element-wise step), sampled columns of dWr
+    over all tokens, and the router term of dx on sampled tokens."""
+    wl = W.DSV3
+    print(f"full-size gate case {wl.name}: T={wl.T} d={wl.d} E={wl.E} k={wl.k}", flush=True)
+    rng = np.random.default_rng(wl.seed)
+    x = W.tokens(wl); wr = W.router_weights(wl); dy = W.out_grad(wl)
+    dt = torch.bfloat16
+    xd, wrd, dyd = to_device(x, dt), to_device(wr, dt), to_device(dy, dt)
+    T, d, E, k = wl.T, wl.d, wl.E, wl.k
+    ws = torch.empty(B.moe_workspace_bytes(B.WS_ROUTER, B.MOE_BF16, T, k, d, wl.f, E, 0), dtype=torch.uint8, device="cuda")
+    logits = torch.full((T, E), 7.0, dtype=torch.float32, device="cuda")
+    B.moe_router_fwd(xd, wrd, logits, ws)
+    ti = torch.empty((T, k), dtype=torch.int32, device="cuda"); tw = torch.empty((T, k), device="cuda")
+    cnt = torch.empty((wl.e_cnt,), dtype=torch.int32, device="cuda")
+    B.moe_route(logits, k, wl.gate_mode, wl.e_lo, wl.e_cnt, ti, tw, cnt)
+    R = int(cnt.sum().item())
+    off = torch.empty((wl.e_cnt + 1,), dtype=torch.int32, device="cuda")
+    perm = torch.empty((R,), dtype=torch.int32, device="cuda"); inv = torch.empty_like(ti)
+    wsd = torch.empty(B.moe_workspace_bytes(B.WS_DISPATCH, B.MOE_BF16, T, k, d, wl.f, wl.e_cnt, R), dtype=torch.uint8, device="cuda")
+    xp = torch.empty((R, d), dtype=dt, device="cuda")
+    B.moe_dispatch(xd, k, ti, None, wl.e_lo, wl.e_cnt, off, perm, inv, False, xp, wsd)
+    o = torch.randn((R, d), device="cuda", dtype=dt)          # stands in for the expert outputs
+    d_o = torch.empty_like(o); dgate = torch.full((T, k), 7.0, device="cuda")
+    B.moe_combine_bwd(dyd, o, inv, tw, d_o, dgate)
+    dlog = torch.full((T, E), 7.0, device="cuda")
+    B.moe_gate_bwd(logits, ti, dgate, wl.gate_mode, dlog)
+    dwr = torch.full((d, E), 7.0, dtype=dt, device="cuda")
+    dx = torch.zeros((T, d), dtype=dt, device="cuda")
+    B.moe_router_bwd(xd, wrd, dlog, dwr, False, dx, False, ws)
+    torch.cuda.synchronize()
+    # logits of sampled tokens
+    rows = np.sort(rng.choice(T, size=512, replace=False))
+    lg = host(logits)
+    assert rel_err(lg[rows], O.router_logits(x[rows], wr)) < 1e-5
+    # selection on the GPU's logits, in full
+    ti_ref, tw_ref, cnt_ref = O.route(lg.astype(np.float32), k, wl.gate_mode, wl.e_lo, wl.e_cnt)
+    assert (host(ti) == ti_ref).all() and (host(cnt) == cnt_ref).all()
+    # dgate of sampled tokens from the GPU's o rows
+    inv_h = host(inv)
+    o_h = host(o)
+    dg_ref = O.gate_grad(dy[rows], o_h, inv_h[rows])
+    dg = host(dgate)
+    assert rel_err(dg[rows], dg_ref) < 2e-2
+    assert not dg[inv_h < 0].any()
+    # gate backward, element-wise: in full from the GPU's dgate
+    dl_ref = O.gate_bwd(lg.astype(np.float32), ti_ref, dg, wl.gate_mode)
+    dl = host(dlog)
+    assert rel_err(dl, dl_ref) < 1e-5
+    # sampled columns of dWr over all tokens; router term of dx on sampled tokens
+    J = np.sort(rng.choice(E, size=6, replace=False))
+    dwr_ref = x.astype(np.float64).T @ dl[:, J]
+    assert rel_err(host(dwr)[:, J], dwr_ref) < 2e-2
+    dx_ref = dl[rows] @ wr.astype(np.float64).T
+    assert rel_err(host(dx)[rows], dx_ref) < 2e-2
