@@ -35,6 +35,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-router", action="store_true", help="skip the trainable-gate kernels (timed after the step)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--chunks", type=int, nargs="*", default=[],
+                    help="also time the token-chunked two-stream schedule with these chunk counts (reported beside "
+                         "the headline value, not inside it)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB device copies (a kernel of known HBM "
                          "traffic) so that a rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE run can be scaled")
@@ -108,6 +111,7 @@ def main():
             kern[name] = dict(avg_ms=ms / n, launches=n)
     # enabling the profiler again starts a new log: the step's figures were read above
     router = None if args.no_router else router_row(B, C, W, torch, wl, dev, buf, R, U, b)
+    chunked = {str(c): chunked_ms(torch, wl, dev, c, args.warmup, args.steps) for c in args.chunks}
     ceilings = measured_ceilings(B, torch)
 
     if args.calibration_copy:
@@ -173,6 +177,8 @@ def main():
     }
     if router:
         out["trainable_gate"] = router
+    if chunked:
+        out["chunked_schedule_ms_per_step"] = chunked
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, logits, dy, args.cpu_seconds)
@@ -222,6 +228,20 @@ def router_row(B, C, W, torch, wl, dev, buf, R, U, b, reps=10):
         out["router_dx"]["GBps"] = (2.0 * T * d * b + T * E * 2 + d * E * b) / (out["router_dx"]["avg_ms"] * 1e-3) / 1e9
     out["total_ms"] = sum(v["avg_ms"] for v in out.values())
     return out
+
+
+def chunked_ms(torch, wl, dev, n_chunks, warmup, steps):
+    """Step time of the token-chunked two-stream schedule (movers of one chunk beside the GEMMs of another)."""
+    from paper_2605_11005_amd.chunked import ChunkedLayer
+    ch = ChunkedLayer(wl, n_chunks)
+    for _ in range(max(warmup, 1)):
+        ch.forward(dev); ch.backward(dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ch.forward(dev); ch.backward(dev)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
 
 
 def measured_ceilings(B, torch):
