@@ -4,4 +4,4 @@ set -e
 cd "$(dirname "$0")"
 exec hipcc --offload-arch=gfx950 -O3 -std=c++17 -fPIC -shared \
   -Xclang -target-feature -Xclang -packed-fp32-ops "$@" \
-  api.hip route.hip plan.hip rowmove.hip expert_f32.hip expert_bf16.hip router.hip probes.hip -o ../libmoe_mi355x.so
+  api.hip route.hip plan.hip rowmove.hip expert_f32.hip expert_bf16.hip router.hip probes.hip alloc.hip -o ../libmoe_mi355x.so

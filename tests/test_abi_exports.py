@@ -11,8 +11,8 @@ from paper_2605_11005_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    src = open(os.path.join(ROOT, "include", "moe.h")).read()
+def _declared(header="moe.h"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src)))
 
@@ -35,6 +35,11 @@ def test_every_declared_symbol_is_exported(lib):
     for n in _declared():
         assert hasattr(lib, n), n
     assert set(_declared()) == set(B.EXPORTS)
+    from paper_2605_11005_amd import alloc as A
+    alloc_names = [n for n in _declared("moe_alloc.h") if n != "moe_alloc_profile_fn"]
+    for n in alloc_names:
+        assert hasattr(lib, n), n
+    assert set(alloc_names) == set(A.EXPORTS)
 
 
 def test_error_strings_and_workspace_sizes(lib):

@@ -1,0 +1,147 @@
+"""Worker-allocation tool: the oracle against what the paper prints and what the mathematics
+fixes, then the C++ tool (through its C ABI) against the oracle.  CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import alloc_oracle as AO
+from paper_2605_11005_amd import alloc as A
+
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "alloc_paper_examples.txt")
+
+
+def _gold():
+    out = {}
+    for line in open(GOLD):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            key, val = line.split(":")
+            out[key.strip()] = val.split()
+    return out
+
+
+# ------------------------------------------------------------------ oracle pins
+def test_oracle_placement_matches_the_papers_example():
+    g = _gold()
+    assert AO.group_layers(8, 2, 0) == [int(v) for v in g["placement L=8 p=2 g=0"]]
+    assert AO.group_layers(8, 2, 1) == [int(v) for v in g["placement L=8 p=2 g=1"]]
+    # a partition of the layers, group sizes differ by at most one
+    for L, p in ((7, 3), (94, 4), (5, 8)):
+        groups = [AO.group_layers(L, p, q) for q in range(p)]
+        assert sorted(itertools.chain(*groups)) == list(range(L))
+        sizes = [len(x) for x in groups]
+        assert max(sizes) - min(sizes) <= 1
+
+
+def test_oracle_costs_reproduce_the_papers_intensities():
+    g = _gold()
+    for (b, S, H, gq, k, De) in ((1, 4096, 4096, 8, 8, 1536), (3, 32768, 2880, 4, 4, 2880)):
+        c = AO.costs(b, S, H, gq, k, De)
+        assert c["I_ffn"] == pytest.approx(float(g["intensity_ffn_over_De"][0]) * De, rel=1e-12)
+        assert c["I_attn"] == pytest.approx((H * (2 + 2 / gq) + 4 * S) / (2 * k), rel=1e-12)
+        assert c["C_f"] == pytest.approx(b * 4 * k * S * H * De) and c["V"] == pytest.approx(b * 2 * S * k * H)
+        # attention is quadratic in S, FFN and volume linear (motivation section)
+        c2 = AO.costs(b, 2 * S, H, gq, k, De)
+        assert c2["C_f"] == pytest.approx(2 * c["C_f"]) and c2["V"] == pytest.approx(2 * c["V"])
+        assert c2["C_a"] > 2 * c["C_a"]
+    assert AO.costs(1, 128, 64, 2, 2, 32, n_mat=3)["C_f"] == pytest.approx(1.5 * AO.costs(1, 128, 64, 2, 2, 32)["C_f"])
+
+
+def test_oracle_bubble_ratio_is_one_fourth_under_the_papers_conditions():
+    g = _gold()
+    base, af = AO.bubbles(PP=4, L=1, v=2, T_a=3.0, T_f=3.0, T_a2a=3.0, T_p2p=0.0, T_m2n=3.0)
+    assert af / base == pytest.approx(float(g["bubble_ratio L=1 equal_times"][0]))
+    assert AO.bubbles(1, 5, 1, 1, 1, 1, 1, 1) == (0.0, 0.0)          # one stage: no bubble
+
+
+def test_oracle_seed_balances_a_symmetric_problem_and_follows_the_load():
+    # equal groups, compute-bound whatever the NIC split: half of the GPUs each, every NIC split ties
+    sym = dict(C_a=1e15, C_f=1e15, V=1e9, P=1e15, B=1e11)
+    s = AO.seed(sym, W=16, M_tot=8)
+    assert s["M"] == 8 and s["T_star"] == pytest.approx(1e15 / (1e15 * 8))
+    assert sorted(s["candidates"]) == [(8, ma) for ma in range(1, 8)]
+    # equal groups, network-bound: the NICs are split evenly and T* is the transfer time
+    net = dict(C_a=1e15, C_f=1e15, V=1e11, P=1e15, B=1e11)
+    s = AO.seed(net, W=16, M_tot=8)
+    assert s["M_a"] == 4 and s["T_star"] == pytest.approx(1e11 / (4 * 1e11))
+    assert all(ma == 4 for (_, ma) in s["candidates"])
+    # three times the attention FLOPs, compute-bound: three quarters of the GPUs
+    heavy = dict(C_a=3e15, C_f=1e15, V=1e3, P=1e15, B=1e11)
+    s = AO.seed(heavy, W=16, M_tot=8)
+    assert s["M"] == 12
+    # T* is the true minimum over the whole grid (eps = 0) and every candidate attains it
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        m = dict(C_a=10 ** rng.uniform(14, 17), C_f=10 ** rng.uniform(14, 17), V=10 ** rng.uniform(9, 12), P=1e15, B=5e10)
+        W, Mt = int(rng.integers(2, 40)), int(rng.integers(2, 20))
+        s = AO.seed(m, W, Mt)
+        grid = [max(AO.stage_times(m, W, Mt, M, Ma)) for M in range(1, W) for Ma in range(1, Mt)]
+        assert s["T_star"] == min(grid)
+        assert all(max(AO.stage_times(m, W, Mt, M, Ma)) == s["T_star"] for (M, Ma) in s["candidates"])
+        # the tie-break can only help the attained fractions
+        best = sum(AO.attained(m, W, Mt, s["M"], s["M_a"]))
+        assert all(best >= sum(AO.attained(m, W, Mt, M, Ma)) - 1e-15 for (M, Ma) in s["candidates"])
+        ua, uf = AO.attained(m, W, Mt, s["M"], s["M_a"])
+        assert 0 < ua <= 1 + 1e-12 and 0 < uf <= 1 + 1e-12
+
+
+def test_oracle_refine_never_gets_worse_and_finds_a_planted_optimum():
+    prof = lambda M, Ma: abs(M - 11) + 0.5 * abs(Ma - 3)
+    rng = np.random.default_rng(0)
+    dM, dMa = rng.integers(-2, 3, 200).tolist(), rng.integers(-2, 3, 200).tolist()
+    m, ma, t = AO.refine(32, 8, 4, 6, dM, dMa, prof)
+    assert (m, ma, t) == (11, 3, 0.0)
+    assert AO.refine(32, 8, 4, 6, [], [], prof) == (4, 6, prof(4, 6))
+    # clipped to the feasible box
+    m, ma, _ = AO.refine(4, 3, 1, 1, [-5, 9], [-5, 9], lambda M, Ma: -M - Ma)
+    assert (m, ma) == (3, 2)
+
+
+# ------------------------------------------------------------------ the tool against the oracle
+def test_tool_matches_oracle_on_random_models():
+    rng = np.random.default_rng(11)
+    for case in range(60):
+        m = dict(C_a=10 ** rng.uniform(13, 17), C_f=10 ** rng.uniform(13, 17), V=10 ** rng.uniform(8, 12),
+                 P=10 ** rng.uniform(14, 15.5), B=10 ** rng.uniform(10, 11.5))
+        W, Mt = int(rng.integers(2, 64)), int(rng.integers(2, 24))
+        eps = 0.0 if case % 2 == 0 else float(10 ** rng.uniform(-6, -2))
+        ref = AO.seed(m, W, Mt, eps)
+        got = A.seed(m, W, Mt, eps)
+        assert (got["M"], got["M_a"]) == (ref["M"], ref["M_a"]), case
+        assert got["T_star"] == ref["T_star"] and got["n_candidates"] == len(ref["candidates"])
+        M, Ma = int(rng.integers(1, W)), int(rng.integers(1, Mt))
+        e = A.evaluate(m, W, Mt, M, Ma)
+        assert (e["T_a"], e["T_f"]) == AO.stage_times(m, W, Mt, M, Ma)
+        assert (e["U_a"], e["U_f"]) == pytest.approx(AO.attained(m, W, Mt, M, Ma), rel=1e-14)
+
+
+def test_tool_costs_placement_bubbles_and_refine_match_oracle():
+    for args in ((1, 4096, 4096, 8, 8, 1536, 2, 2), (2, 8192, 7168, 1, 8, 2048, 3, 2), (1, 100, 64, 4, 2, 48, 2, 4)):
+        ref, got = AO.costs(*args), A.costs(*args)
+        for key in ref:
+            assert got[key] == pytest.approx(ref[key], rel=1e-14), key
+    for L, p in ((8, 2), (7, 3), (94, 4), (3, 5)):
+        for g in range(p):
+            assert A.group_layers(L, p, g) == AO.group_layers(L, p, g)
+    assert A.bubbles(8, 3, 2, 1.5, 2.5, 0.7, 0.1, 0.9) == pytest.approx(AO.bubbles(8, 3, 2, 1.5, 2.5, 0.7, 0.1, 0.9), rel=1e-15)
+    prof = lambda M, Ma: (M - 9) ** 2 + 3 * abs(Ma - 5) + 0.25 * ((M * 7 + Ma) % 3)
+    rng = np.random.default_rng(5)
+    dM, dMa = rng.integers(-3, 4, 150).tolist(), rng.integers(-3, 4, 150).tolist()
+    assert A.refine(40, 12, 20, 2, dM, dMa, prof) == AO.refine(40, 12, 20, 2, dM, dMa, prof)
+
+
+def test_tool_rejects_bad_arguments():
+    from paper_2605_11005_amd.binding import MoeError
+    good = dict(C_a=1e15, C_f=1e15, V=1e9, P=1e15, B=1e11)
+    with pytest.raises(MoeError):
+        A.seed(dict(good, V=0.0), 16, 8)
+    with pytest.raises(MoeError):
+        A.seed(good, 1, 8)
+    with pytest.raises(MoeError):
+        A.evaluate(good, 16, 8, 16, 4)
+    with pytest.raises(MoeError):
+        A.group_layers(8, 2, 2)
+    with pytest.raises(MoeError):
+        A.costs(1, 0, 64, 2, 2, 32)
