@@ -315,12 +315,6 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     total = tile_start[e_cnt];
   }
 
-  // ---- dynamic, XCD-aware tile scheduler.  The list is cut into chunks of 32 consecutive
-  // tiles (an 8 x 4 block of one expert: 8 A panels and 4 B panels); chunk c belongs to XCD
-  // c mod 8 (workgroup b runs on XCD b mod 8), whose workgroups draw tiles from it in order
-  // through one atomic counter per XCD.  Ticket q of XCD x is tile 32*(8*(q/32) + x) + q%32.
-  // The ticket for the next tile is drawn while the current one is computed.  A workgroup whose
-  // queue has run dry moves on to the next XCD's queue.
   // per-lane fragment offsets inside an operand tile (k-step 0)
   int a_off[4], b_off[4];
 #pragma unroll
@@ -375,8 +369,8 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   // tiles (an 8 x 4 block of one expert: 8 A panels and 4 B panels); chunk c belongs to XCD
   // c mod 8 (workgroup b runs on XCD b mod 8), whose workgroups draw tiles from it in order
   // through one atomic counter per XCD.  Ticket q of XCD x is tile 32*(8*(q/32) + x) + q%32.
-  // The ticket for the tile after the next is drawn while the current one is computed.  A
-  // workgroup whose queue has run dry moves on to the next XCD's queue.
+  // The ticket for the next tile is drawn near the end of the current k loop.  A workgroup whose
+  // queue has run dry moves on to the next XCD's queue.
   //
   // next_tile: takes the ticket waiting in *next_q, decodes it into the tile state above and
   // starts the loads of that tile's first k-tiles.  The tile ring must be free when it is

@@ -132,3 +132,53 @@ def test_dispatch_combine_identity_round_trip():
     assert rel_err(host(y1), x.astype(np.float64) * local.sum(1, keepdims=True)) < 1e-2
     assert int(off[-1]) == int(local.sum()) == int(cnt.sum())
     assert not host(y)[local.sum(1) == 0].any()
+
+
+@pytest.mark.parametrize("wl", [W.TINY, W.QWEN.scaled(name="qwen-fwd-only", T=1024, d=128, f=192)], ids=lambda w: w.name)
+def test_forward_only_without_saved_activations(wl):
+    """h1 = h3 = NULL: the forward keeps nothing for the backward; o is bit-identical."""
+    inp = make_inputs(wl)
+    dev, buf = gpu_layer(wl, inp)
+    o2 = torch.full_like(buf.o, 9.0)
+    B.moe_expert_fwd(buf.xp, buf.offsets, dev["w1"], dev["w3"], dev["w2"], None, None, o2, buf.ws_fwd)
+    torch.cuda.synchronize()
+    R = int(buf.offsets[-1])
+    assert torch.equal(o2[:R], buf.o[:R])
+    assert (o2[R:] == 9.0).all(), "rows past R are left untouched"
+
+
+@pytest.mark.parametrize("T", [1, 5, 63])
+def test_bf16_tiny_batches(T):
+    wl = W.DSV3.scaled(name=f"dsv3-T{T}", T=T, d=128, f=64, E=16, e_lo=4, e_cnt=8, k=4)
+    inp = make_inputs(wl)
+    fw, bw = oracle_layer(wl, inp)
+    _, buf = gpu_layer(wl, inp)
+    check_layer(wl, inp, fw, bw, buf)
+
+
+def test_all_experts_selected_and_empty_local_slice():
+    # k == E: every expert is selected by every token
+    wl = W.MIXTRAL.scaled(name="k-equals-E", T=300, d=64, f=64, E=4, e_cnt=4, k=4)
+    inp = make_inputs(wl)
+    fw, bw = oracle_layer(wl, inp)
+    _, buf = gpu_layer(wl, inp)
+    check_layer(wl, inp, fw, bw, buf)
+    assert fw["counts"].tolist() == [300] * 4
+    # a GPU holding no expert of this layer: nothing is routed here, y is zero
+    wl0 = W.QWEN.scaled(name="no-local-expert", T=256, d=64, f=64, E=16, e_lo=5, e_cnt=0, k=2)
+    x = W.tokens(wl0); logits = W.router_logits(wl0)
+    xd = torch.from_numpy(x).cuda().to(torch.bfloat16)
+    ti = torch.empty((wl0.T, wl0.k), dtype=torch.int32, device="cuda"); tw = torch.empty((wl0.T, wl0.k), device="cuda")
+    cnt = torch.empty((0,), dtype=torch.int32, device="cuda")
+    B.moe_route(torch.from_numpy(logits).cuda(), wl0.k, wl0.gate_mode, 5, 0, ti, tw, cnt)
+    off = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    perm = torch.empty((1,), dtype=torch.int32, device="cuda"); inv = torch.empty_like(ti)
+    xp = torch.zeros((1, wl0.d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(B.moe_workspace_bytes(B.WS_DISPATCH, 1, wl0.T, wl0.k, wl0.d, wl0.f, 0, 1), dtype=torch.uint8, device="cuda")
+    B.moe_dispatch(xd, wl0.k, ti, None, 5, 0, off, perm, inv, False, xp, ws)
+    y = torch.full_like(xd, 3.0)
+    B.moe_combine(xp, inv, tw, y)
+    torch.cuda.synchronize()
+    ti_ref, _, _ = O.route(logits, wl0.k, wl0.gate_mode, 5, 0)
+    assert (host(ti) == ti_ref).all() and off.tolist() == [0]
+    assert (host(inv) == -1).all() and not y.any().item()
