@@ -329,6 +329,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   const int n_queues = (G % 8) == 0 ? 8 : 1;
   int queue = blockIdx.x % n_queues;       // the queue this workgroup currently draws from
   int exhausted = 0;                       // queues found empty so far
+  int pos_hint = 0;                        // list position of the last decoded tile
   const uint32_t smem_base = lds_addr(smem);
 
   // ---- state of the tile whose k loop runs next (written by next_tile)
@@ -381,12 +382,12 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     while (true) {
       const int q = __builtin_amdgcn_readfirstlane(*next_q);
       L = 32 * (n_queues * (q >> 5) + queue) + (q & 31);
-      __syncthreads();                       // everyone has read the ticket before it is replaced
-      if (L < total) break;
+      if (L < total) break;                  // (the slot is next written after a whole k loop of barriers)
       // tickets only grow, so this queue is finished: help the next XCD's queue (work stealing
       // at the tail of the schedule), stop once every queue has been seen empty
       if (++exhausted == n_queues) return false;
       queue = (queue + 1) % n_queues;
+      __syncthreads();                       // everyone has read the ticket before it is replaced
       if (tid == 0) *next_q = atomicAdd(p.sched + queue, 1);
       __syncthreads();
     }
@@ -396,11 +397,23 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     int mt, nt;
     {
       int li, mte;
-      int a = 0, c = e_cnt;                      // largest position with tile_start[pos] <= L
-      while (c - a > 1) {
-        int mid = (a + c) >> 1;
-        if (tile_start[mid] <= L) a = mid; else c = mid;
+      // largest position with tile_start[pos] <= L: tickets of a queue ascend, so it is usually
+      // the position of the previous tile or the one after it; otherwise a binary search
+      int a = pos_hint;
+      {
+        const int t0 = tile_start[a], t1 = tile_start[a + 1], t2 = tile_start[min(a + 2, e_cnt)];
+        if (L >= t1 && L < t2) a = a + 1;
+        else if (L < t0 || L >= t1) {
+          a = 0;
+          int c = e_cnt;
+          while (c - a > 1) {
+            int mid = (a + c) >> 1;
+            if (tile_start[mid] <= L) a = mid; else c = mid;
+          }
+        }
       }
+      a = __builtin_amdgcn_readfirstlane(a);
+      pos_hint = a;
       li = __builtin_amdgcn_readfirstlane(L - tile_start[a]);
       e = __builtin_amdgcn_readfirstlane((int)order[a]);
       lo = __builtin_amdgcn_readfirstlane(offs[e]);
@@ -448,6 +461,8 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       issue_tile(0); issue_tile(1); issue_tile(2);
 #pragma unroll
       for (int q = 0; q < 4; ++q) issue_one(3, q);
+    } else {
+      __syncthreads();   // a tile without a k loop has no barrier between this read of the ticket and its replacement
     }
     return true;
   };
