@@ -142,6 +142,88 @@ __global__ void reduce_chunks(const float* __restrict__ partial, int chunks, siz
   }
 }
 
+// dx[t,c] (=|+=) sum_e dl[t,e] * Wr[c,e] for a small number of experts (the plain path's router term of dx):
+// one thread per 4 consecutive columns c, whose 4*E weights are contiguous in memory; the token's
+// dlogits row sits in LDS.  grid = (column groups, tokens).
+template <typename TW>
+__global__ __launch_bounds__(256) void router_dx_small_e(const float* __restrict__ dl, const TW* __restrict__ wr,
+                                                        TW* __restrict__ dx, int d, int E, int beta) {
+  __shared__ float row[MOE_MAX_EXPERTS];
+  const int t = blockIdx.y;
+  for (int e = threadIdx.x; e < E; e += 256) row[e] = dl[(size_t)t * E + e];
+  __syncthreads();
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c0 >= d) return;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (c0 + i >= d) break;
+    const TW* w = wr + (size_t)(c0 + i) * E;
+    float s = 0.f;
+    for (int e = 0; e < E; ++e) s += row[e] * ldf(w, e);
+    acc[i] = s;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (c0 + i >= d) break;
+    const size_t idx = (size_t)t * d + c0 + i;
+    stf(dx, idx, beta ? ldf(dx, idx) + acc[i] : acc[i]);
+  }
+}
+
+// logits[t,e] = sum_c x[t,c] * Wr[c,e] for a small number of experts: one block per token, eight
+// experts per pass (their weights are contiguous in a row of Wr), columns strided over the threads,
+// sums reduced lanes -> wavefront -> block in a fixed order.
+template <typename TX>
+__global__ __launch_bounds__(256) void router_fwd_small_e(const TX* __restrict__ x, const TX* __restrict__ wr,
+                                                         float* __restrict__ logits, int d, int E) {
+  __shared__ float red[8][4];
+  const int t = blockIdx.x, lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+  for (int e0 = 0; e0 < E; e0 += 8) {
+    const int ne = E - e0 < 8 ? E - e0 : 8;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    if (sizeof(TX) == 2 && (E & 7) == 0 && (d & 7) == 0) {
+      // bf16, whole groups of eight: 16-byte loads of eight columns of x and of each column's eight weights
+      const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
+      const uint16_t* wb = reinterpret_cast<const uint16_t*>(wr);
+      for (int c8 = threadIdx.x * 8; c8 < d; c8 += 2048) {
+        const uint4 xq = *reinterpret_cast<const uint4*>(xb + (size_t)t * d + c8);
+        const uint32_t* xu = reinterpret_cast<const uint32_t*>(&xq);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float xv = (j & 1) ? bf16hi(xu[j >> 1]) : bf16lo(xu[j >> 1]);
+          const uint4 wq = *reinterpret_cast<const uint4*>(wb + (size_t)(c8 + j) * E + e0);
+          const uint32_t* wu = reinterpret_cast<const uint32_t*>(&wq);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += xv * bf16lo(wu[i]);
+            acc[2 * i + 1] += xv * bf16hi(wu[i]);
+          }
+        }
+      }
+    } else {
+      for (int c = threadIdx.x; c < d; c += 256) {
+        const float xv = ldf(x, (size_t)t * d + c);
+        const TX* w = wr + (size_t)c * E + e0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (i < ne) acc[i] += xv * ldf(w, i);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float v = wave_sum_f(acc[i]);
+      if (lane == 0) red[i][wave] = v;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < ne)
+      logits[(size_t)t * E + e0 + threadIdx.x] = (red[threadIdx.x][0] + red[threadIdx.x][1]) + (red[threadIdx.x][2] + red[threadIdx.x][3]);
+    __syncthreads();
+  }
+}
+
 __global__ void round_to_bf16(const float* __restrict__ in, bf16_t* __restrict__ out, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     out[i] = f32_to_bf16(in[i]);
@@ -338,13 +420,20 @@ int launch_router_fwd(const void* x, const void* wr, int dtype, int T, int d, in
   if (T == 0) return MOE_OK;
   if (mfma_shape(dtype, T, d, E)) return launch_router_fwd_bf16(x, wr, T, d, E, logits, (int32_t*)ws, s);
   ProfScope prof(MOE_K_ROUTER_FWD, s);
-  dim3 grid(tiles(E, TN), tiles(T, TM)), blk(256);
-  if (dtype == MOE_BF16)
-    hipLaunchKernelGGL((gemm_rows_valu<bf16_t, bf16_t, float>), grid, blk, 0, s, (const bf16_t*)x, d, (const bf16_t*)wr,
-                       (long)E, 1L, logits, E, T, E, d, 0);
-  else
-    hipLaunchKernelGGL((gemm_rows_valu<float, float, float>), grid, blk, 0, s, (const float*)x, d, (const float*)wr,
-                       (long)E, 1L, logits, E, T, E, d, 0);
+  if (E <= 64) {
+    if (dtype == MOE_BF16)
+      hipLaunchKernelGGL((router_fwd_small_e<bf16_t>), dim3(T), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)wr, logits, d, E);
+    else
+      hipLaunchKernelGGL((router_fwd_small_e<float>), dim3(T), dim3(256), 0, s, (const float*)x, (const float*)wr, logits, d, E);
+  } else {
+    dim3 grid(tiles(E, TN), tiles(T, TM)), blk(256);
+    if (dtype == MOE_BF16)
+      hipLaunchKernelGGL((gemm_rows_valu<bf16_t, bf16_t, float>), grid, blk, 0, s, (const bf16_t*)x, d, (const bf16_t*)wr,
+                         (long)E, 1L, logits, E, T, E, d, 0);
+    else
+      hipLaunchKernelGGL((gemm_rows_valu<float, float, float>), grid, blk, 0, s, (const float*)x, d, (const float*)wr,
+                         (long)E, 1L, logits, E, T, E, d, 0);
+  }
   HIP_CHECK_LAUNCH();
   return MOE_OK;
 }
@@ -433,14 +522,23 @@ int launch_router_bwd(const void* x, const void* wr, const float* dlogits, int d
   }
   if (dx && T > 0) {
     ProfScope prof(MOE_K_ROUTER_DX, s);
-    // dx[t,n] (+)= sum_e dl[t,e] * Wr[n,e] : B(k = e, n) = Wr[n*E + e]
-    dim3 grid(tiles(d, TN), tiles(T, TM)), blk(256);
-    if (dtype == MOE_BF16)
-      hipLaunchKernelGGL((gemm_rows_valu<float, bf16_t, bf16_t>), grid, blk, 0, s, dlogits, E, (const bf16_t*)wr, 1L, (long)E,
-                         (bf16_t*)dx, d, T, d, E, dx_acc);
-    else
-      hipLaunchKernelGGL((gemm_rows_valu<float, float, float>), grid, blk, 0, s, dlogits, E, (const float*)wr, 1L, (long)E,
-                         (float*)dx, d, T, d, E, dx_acc);
+    if (E <= 64) {
+      // a handful of experts: per-token dot products against contiguous weight rows
+      dim3 grid(tiles(d, 1024), T), blk(256);
+      if (dtype == MOE_BF16)
+        hipLaunchKernelGGL((router_dx_small_e<bf16_t>), grid, blk, 0, s, dlogits, (const bf16_t*)wr, (bf16_t*)dx, d, E, dx_acc);
+      else
+        hipLaunchKernelGGL((router_dx_small_e<float>), grid, blk, 0, s, dlogits, (const float*)wr, (float*)dx, d, E, dx_acc);
+    } else {
+      // dx[t,n] (+)= sum_e dl[t,e] * Wr[n,e] : B(k = e, n) = Wr[n*E + e]
+      dim3 grid(tiles(d, TN), tiles(T, TM)), blk(256);
+      if (dtype == MOE_BF16)
+        hipLaunchKernelGGL((gemm_rows_valu<float, bf16_t, bf16_t>), grid, blk, 0, s, dlogits, E, (const bf16_t*)wr, 1L, (long)E,
+                           (bf16_t*)dx, d, T, d, E, dx_acc);
+      else
+        hipLaunchKernelGGL((gemm_rows_valu<float, float, float>), grid, blk, 0, s, dlogits, E, (const float*)wr, 1L, (long)E,
+                           (float*)dx, d, T, d, E, dx_acc);
+    }
     HIP_CHECK_LAUNCH();
   }
   return MOE_OK;
