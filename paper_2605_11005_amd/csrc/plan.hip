@@ -2,7 +2,8 @@
 //
 // Three small kernels, no order-dependent atomics, so perm/inv are unique and reproducible:
 //   1. plan_hist    -- every wavefront owns CHUNK consecutive slots and writes the histogram
-//                      of their local experts to ws_hist[chunk][e].
+//                      of their local experts to ws_hist[e][chunk] (chunks contiguous per expert,
+//                      so that the scan reads coalesced).
 //   2. plan_scan    -- one block, one wavefront per expert: an exclusive running sum over the chunks
 //                      (-> first row of that expert inside each chunk), then the exclusive
 //                      prefix over experts (-> offsets), clamped to cap with a status word.
@@ -31,10 +32,10 @@ __global__ __launch_bounds__(64) void plan_hist(const int32_t* __restrict__ topk
     }
   }
   __syncthreads();
-  for (int i = lane; i < e_cnt; i += WAVE) ws_hist[(size_t)blockIdx.x * e_cnt + i] = h[i];
+  for (int i = lane; i < e_cnt; i += WAVE) ws_hist[(size_t)i * gridDim.x + blockIdx.x] = h[i];   // [expert][chunk]
 }
 
-// ws_hist[c][e] becomes the first row (before the expert's offset is added) of expert e in chunk c.
+// ws_hist[e][c] becomes the first row (before the expert's offset is added) of expert e in chunk c.
 // One wavefront per expert: 64 chunks at a time, exclusive scan by lane shuffles, carry across
 // groups of 64.
 __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ ws_hist, int n_chunks, int e_cnt, int cap,
@@ -43,17 +44,27 @@ __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ ws_hist,
   const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE, n_waves = blockDim.x / WAVE;
   for (int e = wave; e < e_cnt; e += n_waves) {
     int carry = 0;
-    for (int c0 = 0; c0 < n_chunks; c0 += WAVE) {
-      const int c = c0 + lane;
-      const int v = c < n_chunks ? ws_hist[(size_t)c * e_cnt + e] : 0;
-      int incl = v;
+    // eight groups of 64 chunks per batch: all loads of a batch are issued before the first scan,
+    // so a batch costs one memory round trip instead of eight
+    for (int b0 = 0; b0 < n_chunks; b0 += 8 * WAVE) {
+      int v[8];
 #pragma unroll
-      for (int off = 1; off < WAVE; off <<= 1) {
-        int t = __shfl_up(incl, off, WAVE);
-        if (lane >= off) incl += t;
+      for (int g = 0; g < 8; ++g) {
+        const int c = b0 + g * WAVE + lane;
+        v[g] = c < n_chunks ? ws_hist[(size_t)e * n_chunks + c] : 0;
       }
-      if (c < n_chunks) ws_hist[(size_t)c * e_cnt + e] = carry + incl - v;
-      carry += __shfl(incl, WAVE - 1, WAVE);
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        const int c = b0 + g * WAVE + lane;
+        int incl = v[g];
+#pragma unroll
+        for (int off = 1; off < WAVE; off <<= 1) {
+          int t = __shfl_up(incl, off, WAVE);
+          if (lane >= off) incl += t;
+        }
+        if (c < n_chunks) ws_hist[(size_t)e * n_chunks + c] = carry + incl - v[g];
+        carry += __shfl(incl, WAVE - 1, WAVE);
+      }
     }
     if (lane == 0) total[e] = carry;
   }
@@ -85,7 +96,7 @@ __global__ __launch_bounds__(64) void plan_scatter(const int32_t* __restrict__ t
   extern __shared__ int32_t run[];
   const int lane = threadIdx.x;
   const int32_t* ebase = ws_hist + (size_t)n_chunks * e_cnt;
-  for (int i = lane; i < e_cnt; i += WAVE) run[i] = ebase[i] + ws_hist[(size_t)blockIdx.x * e_cnt + i];
+  for (int i = lane; i < e_cnt; i += WAVE) run[i] = ebase[i] + ws_hist[(size_t)i * n_chunks + blockIdx.x];
   __syncthreads();
   const int base = blockIdx.x * CHUNK;
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
