@@ -24,6 +24,8 @@ CASES = [
     W.QWEN.scaled(name="narrow-k", T=700, d=64, f=64),                       # two k-tiles only
     W.DSV3.scaled(name="many-experts", T=1024, d=64, f=128, E=512, e_lo=100, e_cnt=300, k=4),
     W.TINY.scaled(name="fp32-many-experts", T=200, d=32, f=48, E=400, e_lo=0, e_cnt=400, k=5),
+    # the documented limits: 1024 experts, all local, top-64
+    W.DSV3.scaled(name="max-experts-topk", T=256, d=64, f=64, E=1024, e_lo=0, e_cnt=1024, k=64),
     # one expert with far more rows than a workgroup's share: its weight gradients are cut along the rows
     W.MIXTRAL.scaled(name="one-hot-expert", T=5000, d=128, f=192, E=1, e_cnt=1, k=1),
     W.QWEN.scaled(name="hot-and-cold", T=4096, d=320, f=192, E=24, e_lo=0, e_cnt=24, k=2, zipf_s=2.5),
