@@ -861,12 +861,15 @@ constexpr size_t WGRAD_PLAN_BYTES = 2 * MOE_MAX_LOCAL * 4;
 
 template <int MODE>
 int launch_gg(const GArgs& a, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
+  // the LDS opt-in is a per-device attribute of the kernel
+  static bool attr_set[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_EHIP;
+  if (!attr_set[dev]) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gg_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             SMEM_BYTES) != hipSuccess)
       return MOE_EHIP;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   int grid = device_cu_count();
   ProfScope prof(MODE == RL ? MOE_K_ROUTER_FWD : MODE == RW ? MOE_K_ROUTER_DW : MODE == RX ? MOE_K_ROUTER_DX : MOE_K_UP + MODE, s);
