@@ -209,7 +209,7 @@ int moe_gate_bwd(const float* logits, const int32_t* topk_idx, const float* dgat
  *   dwr, dx of type dtype; dlogits [T,E] float.  dwr_accumulate / dx_accumulate: 0 overwrite,
  *   1 add to the existing contents (dx_accumulate = 1 adds the router term to the gradient that
  *   the expert path left in dx).  Either output may be NULL to skip it.
- *   bf16: dlogits is rounded to bf16 for the matrix cores when E % 32 == 0 and d % 64 == 0
+ *   bf16: dlogits is rounded to bf16 for the matrix cores when E % 64 == 0 and d % 64 == 0
  *   (fp32 accumulation over T in fixed-size chunks, chunk sums added in fp32); other shapes
  *   take a plain fp32 path.  ws: moe_workspace_bytes(MOE_WS_ROUTER).
  */

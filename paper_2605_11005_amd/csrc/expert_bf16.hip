@@ -12,11 +12,15 @@
 // 128x128 per wavefront = 4x4 MFMA blocks (256 accumulator registers), one wavefront per SIMD.
 //
 // Data path: global memory -> LDS directly (global_load_lds_dwordx4, 16 bytes per lane, no
-// staging registers), through a ring of four 32 KB stages, so up to three k-tiles (96 KB per
-// CU) are in flight while one is being multiplied.  Because a wavefront's 64 lanes always
-// land on 1 KB of consecutive LDS, bank conflicts are avoided by choosing WHICH global chunk
-// each lane fetches (an XOR swizzle of the chunk index), not by padding:
-//   K-contiguous operand tile  [256 rows][4 chunks of 8 k]   chunk' = chunk ^ ((row>>2)&3)
+// staging registers), through a 128 KB ring (four k-tiles of both operands), so up to three
+// k-tiles (96 KB per CU) are in flight while one is being multiplied.  Every load fetches whole
+// 128-byte cache lines where the layout allows it: the K-contiguous operand A of the ragged-M
+// shapes is fetched two k-tiles at a time (128 bytes per row) into two double stages, because a
+// panel walked in 64-byte pieces crosses the L2-to-CU path twice.  Because a wavefront's 64
+// lanes always land on 1 KB of consecutive LDS, bank conflicts are avoided by choosing WHICH
+// global chunk each lane fetches (an XOR swizzle of the chunk index), not by padding:
+//   K-contiguous A, two k-tiles [256 rows][8 chunks of 8 k]  chunk' = chunk ^ ((row>>1)&7)
+//   K-contiguous B, one k-tile  [256 rows][4 chunks of 8 k]  chunk' = chunk ^ ((row>>2)&3)
 //   transposed operand tile    2 x [32 k][16 chunks of 8 n]  chunk' = chunk ^ (4*(k&3))
 // (LDS has 64 four-byte banks: the 16 lanes served together by a 16-byte read, or the 32 lanes
 // of an 8-byte transposing read, must cover 256 distinct bytes modulo 256.)
@@ -118,7 +122,7 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
-// ---- K-contiguous operand (source rows are tile rows; a k-tile is 64 contiguous bytes) ---
+// ---- K-contiguous operand B (source rows are tile rows; a k-tile is 64 contiguous bytes) -
 // Wavefront w issues 4 loads per k-tile; load j covers LDS chunks [(4w+j)*64, +64):
 // row = 16*(4w+j) + lane/4, LDS slot = lane%4, logical chunk = slot ^ ((row>>2)&3).
 // Rows past the valid range re-read the last valid row (their products land in output rows
@@ -138,6 +142,31 @@ struct KcIssue {
   }
   __device__ __forceinline__ void issue1(int j, uint32_t oper_lds, int wave, long kofs) const {
     dma16(base + kofs, voff[j], oper_lds + (4 * wave + j) * 1024);
+  }
+};
+
+// ---- K-contiguous operand A of the ragged-M shapes, fetched two k-tiles at a time ----------
+// A 64-byte piece is half a cache line, and walking a panel in such pieces moves every line
+// from L2 to the CU twice (a load stream of 64-byte pieces sustains half the rate of one of
+// 128-byte pieces).  So operand A lives in two double stages of [256 rows][128 bytes] = k-tiles
+// 2p and 2p+1 of pair p, filled by 8 loads per wavefront that each fetch whole lines:
+// load q covers LDS chunks [(8w+q)*64, +64): row = 8*(8w+q) + lane/8, LDS slot = lane%8,
+// logical chunk = slot ^ ((row>>1)&7)  (chunks 0..3: k-tile 2p, 4..7: k-tile 2p+1).
+struct KcPairIssue {
+  const bf16_t* base;      // wave-uniform: first row of the tile
+  uint32_t voff[8];        // byte offset of this lane's chunk in load q
+  __device__ __forceinline__ void setup(const bf16_t* base_, long ld, int rows_valid, int wave, int lane) {
+    base = base_;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int rl = 8 * (8 * wave + q) + (lane >> 3);
+      const int c = (lane & 7) ^ ((rl >> 1) & 7);
+      const int r = rl > rows_valid - 1 ? rows_valid - 1 : rl;
+      voff[q] = (uint32_t)(r * ld * 2 + c * 16);
+    }
+  }
+  __device__ __forceinline__ void issue1(int q, uint32_t dstage_lds, int wave, long kofs) const {
+    dma16(base + kofs, voff[q], dstage_lds + (8 * wave + q) * 1024);
   }
 };
 
@@ -179,6 +208,11 @@ template <int V> struct IntC { static constexpr int value = V; };
 // (k-step 1 is k-step 0 with bit 5 flipped: the swizzle is an XOR, not an addition)
 __device__ __forceinline__ int kc_frag_off(int row, int lane, int s) {
   return row * 64 + (((2 * s + (lane >> 5)) ^ ((row >> 2) & 3)) << 4);
+}
+// Double stage of operand A: byte offset of (row, k-tile parity h, k-step s) =
+// row*128 + ((4h + 2s + (l>>5)) ^ ((row>>1)&7))*16; h and s enter as XORs of 64 and 32.
+__device__ __forceinline__ int kcp_frag_off(int row, int lane) {
+  return row * 128 + (((lane >> 5) ^ ((row >> 1) & 7)) << 4);
 }
 // Transposed tile: two 8-byte transposing reads (k 0..3 and 4..7 of the lane's group).  Within
 // each group of 16 lanes, lane i supplies the address of T[kb + i/4][nb16 + 4*(i%4) ..+3] and
@@ -315,14 +349,19 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     total = tile_start[e_cnt];
   }
 
-  // per-lane fragment offsets inside an operand tile (k-step 0)
+  // LDS ring.  Ragged-K shapes: four stages of [A tile | B tile].  Ragged-M shapes (PAIR): operand A
+  // in two double stages of 32 KB (k-tiles 2p, 2p+1) at 0, operand B in four 16 KB stages at 64 KB.
+  constexpr bool PAIR = !TR::RAGGED_K;
+  static_assert(PAIR == !TR::A_TRANS, "operand A is K-contiguous exactly in the ragged-M shapes");
+  constexpr int B_REGION = PAIR ? NSTAGE * OPER_BYTES : OPER_BYTES;
+  // per-lane fragment offsets inside an operand tile (k-step 0; k-tile 2p of a double stage)
   int a_off[4], b_off[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int arow = wm * 128 + i * 32;
     const int brow = TR::DUAL ? (i < 2 ? 0 : 128) + wn * 64 + (i & 1) * 32 : wn * 128 + i * 32;
-    a_off[i] = TR::A_TRANS ? tr_frag_off(arow, lane) : kc_frag_off(arow + (lane & 31), lane, 0);
-    b_off[i] = OPER_BYTES + (TR::B_TRANS ? tr_frag_off(brow, lane) : kc_frag_off(brow + (lane & 31), lane, 0));
+    a_off[i] = TR::A_TRANS ? tr_frag_off(arow, lane) : kcp_frag_off(arow + (lane & 31), lane);
+    b_off[i] = B_REGION + (TR::B_TRANS ? tr_frag_off(brow, lane) : kc_frag_off(brow + (lane & 31), lane, 0));
   }
 
   const int G = gridDim.x;
@@ -338,28 +377,39 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   int nk0 = 0, nk = 0;    // k-tiles in segment 0 / in total
   int row0 = 0;           // first output row (global row for ragged-M, i for the weight gradients)
   int row_end = 0;        // one past the last valid output row
-  KcIssue ia_kc, ib_kc;
+  KcPairIssue ia_kp;
+  KcIssue ib_kc;
   TrIssue ia_tr, ib_tr;
 
   // One of the 8 loads (q = 0..3: operand A, 4..7: operand B) of k-tile kt.  kt is clamped to
   // the last tile, so every iteration issues the same number of loads and the vmcnt
   // arithmetic below is uniform; the surplus loads re-fetch the last tile into a free stage.
-  auto issue_one = [&](int kt, int q) {
+  auto issue_one = [&](int kt, int q) {       // ragged-K shapes
     if (kt > nk - 1) kt = nk - 1;
     const uint32_t st = smem_base + (kt & (NSTAGE - 1)) * STAGE_BYTES;
     const int j = q & 3;
-    if (TR::RAGGED_K) {
-      const long k0 = (long)lo + kt * BK;
-      const int k_last_rel = hi - 1 - lo - kt * BK;
-      if (q < 4) ia_tr.template issue1<true>(j, st, wave, lane, k0, k_last_rel);
-      else ib_tr.template issue1<true>(j, st + OPER_BYTES, wave, lane, k0, k_last_rel);
-    } else {
-      const bool seg1 = MODE == DX && kt >= nk0;
-      const int k0 = (seg1 ? kt - nk0 : kt) * BK;
-      if (q < 4) ia_kc.issue1(j, st, wave, k0 + (seg1 ? p.A1 - p.A0 : 0));
-      else if (TR::B_TRANS) ib_tr.template issue1<false>(j, st + OPER_BYTES, wave, lane, k0, 0);
-      else ib_kc.issue1(j, st + OPER_BYTES, wave, k0 + (seg1 ? p.B1 - p.B0 : 0));
-    }
+    const long k0 = (long)lo + kt * BK;
+    const int k_last_rel = hi - 1 - lo - kt * BK;
+    if (q < 4) ia_tr.template issue1<true>(j, st, wave, lane, k0, k_last_rel);
+    else ib_tr.template issue1<true>(j, st + OPER_BYTES, wave, lane, k0, k_last_rel);
+  };
+  // Ragged-M shapes: one of the 8 loads of operand A's pair pj (k-tiles 2pj, 2pj+1; K is a
+  // multiple of 64 per segment, so a pair never straddles DX's two segments) and one of the 4
+  // loads of operand B's k-tile kt.  Both indices are clamped like kt above.
+  auto issue_a_pair = [&](int pj, int q) {
+    if (pj > (nk >> 1) - 1) pj = (nk >> 1) - 1;
+    const int kt0 = 2 * pj;
+    const bool seg1 = MODE == DX && kt0 >= nk0;
+    const long kofs = (long)(seg1 ? kt0 - nk0 : kt0) * BK + (seg1 ? p.A1 - p.A0 : 0);
+    ia_kp.issue1(q, smem_base + (pj & 1) * (2 * OPER_BYTES), wave, kofs);
+  };
+  auto issue_b = [&](int kt, int j) {
+    if (kt > nk - 1) kt = nk - 1;
+    const uint32_t st = smem_base + B_REGION + (kt & (NSTAGE - 1)) * OPER_BYTES;
+    const bool seg1 = MODE == DX && kt >= nk0;
+    const int k0 = (seg1 ? kt - nk0 : kt) * BK;
+    if (TR::B_TRANS) ib_tr.template issue1<false>(j, st, wave, lane, k0, 0);
+    else ib_kc.issue1(j, st, wave, k0 + (seg1 ? p.B1 - p.B0 : 0));
   };
   auto issue_tile = [&](int kt) {
 #pragma unroll
@@ -453,14 +503,25 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       row_end = hi;
       nk0 = p.K / BK;
       nk = MODE == DX ? 2 * nk0 : nk0;
-      ia_kc.setup(p.A0 + (size_t)row0 * p.lda, p.lda, hi - row0, wave, lane);
+      ia_kp.setup(p.A0 + (size_t)row0 * p.lda, p.lda, hi - row0, wave, lane);
       if (TR::B_TRANS) ib_tr.setup(p.B0 + (size_t)e * p.b_es, p.B1 + (size_t)e * p.b_es, TR::DUAL, p.ldb, n0, p.N, wave, lane);
       else ib_kc.setup(p.B0 + (size_t)e * p.b_es + (size_t)n0 * p.ldb, p.ldb, p.N - n0, wave, lane);
     }
     if (nk > 0) {
-      issue_tile(0); issue_tile(1); issue_tile(2);
+      if (PAIR) {       // what the k loop's iterations -2 and -1 would have issued, in its order
 #pragma unroll
-      for (int q = 0; q < 4; ++q) issue_one(3, q);
+        for (int q = 0; q < 8; ++q) issue_a_pair(0, q);
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) issue_b(t, j);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) issue_a_pair(1, q);
+      } else {
+        issue_tile(0); issue_tile(1); issue_tile(2);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) issue_one(3, q);
+      }
     } else {
       __syncthreads();   // a tile without a k loop has no barrier between this read of the ticket and its replacement
     }
@@ -494,11 +555,12 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     // MFMAs consume them: A0, B0, B1, B2, B3, A1, A2, A3.
     bf16x8 fa[2][4], fb[2][4];
     auto frag_op = [&](int h, int kt, int s, int o) {
-      const char* st = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
+      const char* st = smem + (kt & (NSTAGE - 1)) * (PAIR ? OPER_BYTES : STAGE_BYTES);
       const bool is_a = o == 0 || o >= 5;
       const int idx = o == 0 ? 0 : (o >= 5 ? o - 4 : o - 1);
       if (is_a) {
-        const char* q = st + (TR::A_TRANS ? a_off[idx] + s * 4096 : a_off[idx] ^ (s * 32));
+        const char* q = TR::A_TRANS ? st + a_off[idx] + s * 4096
+                                    : smem + ((kt >> 1) & 1) * (2 * OPER_BYTES) + (a_off[idx] ^ ((kt & 1) * 64 + s * 32));
         fa[h][idx] = TR::A_TRANS ? lds_frag_tr(q) : lds_frag_kc(q);
       } else {
         const char* q = st + (TR::B_TRANS ? b_off[idx] + s * 4096 : b_off[idx] ^ (s * 32));
@@ -522,19 +584,21 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       }
     };
 
-    // ---- k loop.  Ring of four stages; at the barrier of iteration kt every wavefront has
-    // all fragments of tile kt in registers, so stage kt%4 is free for tile kt+4, and tile
-    // kt+1 has landed.  Loads are spread evenly over the iteration -- one per four MFMAs -- so
-    // that the CU's address unit (one 64-lane load per ~24 cycles, shared by the four
-    // wavefronts) never backs up into the issue stream: the first half issues operand B of
-    // tile kt+3, the second half operand A of tile kt+4.  Issue order is A(t),B(t),A(t+1),..;
-    // at the barrier the loads after B(kt+1) are A,B(kt+2) and A,B(kt+3): 16 may remain.
+    // ---- k loop.  At the barrier of iteration kt every wavefront has all fragments of tile kt
+    // in registers, so the LDS that held it is free, and tile kt+1 has landed.  Loads are spread
+    // evenly over the iteration -- one per four MFMAs -- so that the CU's address unit (one
+    // 64-lane load per ~24 cycles, shared by the four wavefronts) never backs up into the issue
+    // stream.  Ragged-K shapes (k_loop): four stages, the first half issues operand B of tile
+    // kt+3, the second half operand A of tile kt+4; issue order is A(t),B(t),A(t+1),..; at the
+    // barrier the loads after B(kt+1) are A,B(kt+2) and A,B(kt+3): 16 may remain.  Ragged-M shapes:
+    // k_loop_pair below.
     // The instruction order inside an iteration is fixed by hand (scheduling fences after every
     // MFMA pair): 16 MFMAs of k-step 0 with the 8 fragment reads of k-step 1 between them,
     // barrier, 16 MFMAs of k-step 1 with the next tile's first fragment reads between them.
-    // The first 28 loads (k-tiles 0..2 and operand A of k-tile 3) were issued by next_tile; the
-    // stores of the previous tile's epilogue were issued after them and share the counter, so
-    // the first wait is for everything.
+    // The first loads (28: k-tiles 0..2 and operand A of k-tile 3; ragged-M shapes 24: A's pair
+    // 0 and half of pair 1, B's k-tiles 0..2) were issued by next_tile; the stores of the previous
+    // tile's epilogue were issued after them and share the counter, so the first wait is for
+    // everything.
     if (nk > 0) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
@@ -577,14 +641,65 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
         }
       }
     };
-    int mv = 4;
-    if (!TR::RAGGED_K) {
+    // Ragged-M shapes: the same iteration, two k-tiles per trip (nk is even).  Operand A arrives
+    // in pairs of k-tiles, operand B one k-tile at a time in its own four stages, and the loads
+    // stay one per four MFMAs: an even iteration kt issues the second half of A's pair kt/2+1,
+    // then (after its barrier) B of tile kt+3; the odd one B of tile kt+3, then the first half
+    // of A's pair (kt-1)/2+2, whose double stage its barrier has just freed.  Issue order is
+    // .. B(2j+1) | B(2j+2) A(j+1)a | A(j+1)b B(2j+3) | B(2j+4) A(j+2)a | ..: at the barrier of
+    // an even iteration 2j (tile 2j+1 must have landed) the 12 loads after B(2j+1) may remain,
+    // at the barrier of an odd one the 8 after A(j+1)b.
+    auto k_loop_pair = [&](auto mv_tag) {
+      constexpr int MV = decltype(mv_tag)::value;
+      auto live = [](int o) { return MV == 4 || (MV == 2 && o <= 5); };
+      auto iteration = [&](int kt, auto odd_tag) {
+        constexpr bool ODD = decltype(odd_tag)::value != 0;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < 16; m += 2) {
+          if (m < 4 * MV) mfma_one(0, m);
+          if (m < 8) {
+            if (live(m)) frag_op(1, kt, 1, m);
+            if (live(m + 1)) frag_op(1, kt, 1, m + 1);
+          }
+          if (m < 4 * MV) mfma_one(0, m + 1);
+          if ((m & 3) == 2) {
+            if (ODD) issue_b(kt + 3, m >> 2);
+            else issue_a_pair((kt >> 1) + 1, 4 + (m >> 2));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (ODD) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < 16; m += 2) {
+          if (m < 4 * MV) mfma_one(1, m);
+          if (live(m >> 1)) frag_op(0, kt + 1, 0, m >> 1);
+          if (m < 4 * MV) mfma_one(1, m + 1);
+          if ((m & 3) == 2) {
+            if (ODD) issue_a_pair((kt >> 1) + 2, m >> 2);
+            else issue_b(kt + 3, m >> 2);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      for (int kt = 0; kt < nk; kt += 2) {
+        if (kt == kt_draw && tid == 0) my_ticket = atomicAdd(p.sched + queue, 1);
+        iteration(kt, IntC<0>{});
+        iteration(kt + 1, IntC<1>{});
+      }
+    };
+    if (TR::RAGGED_K) {
+      k_loop(IntC<4>{});
+    } else {
       const int rows_left = row_end - (row0 + wm * 128);
-      mv = rows_left > 64 ? 4 : (rows_left > 0 ? 2 : 0);
+      const int mv = rows_left > 64 ? 4 : (rows_left > 0 ? 2 : 0);
+      if (mv == 4) k_loop_pair(IntC<4>{});
+      else if (mv == 2) k_loop_pair(IntC<2>{});
+      else k_loop_pair(IntC<0>{});
     }
-    if (mv == 4) k_loop(IntC<4>{});
-    else if (mv == 2) k_loop(IntC<2>{});
-    else k_loop(IntC<0>{});
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     if (tid == 0) *next_q = my_ticket;
     __syncthreads();
@@ -957,7 +1072,7 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   return MOE_OK;
 }
 
-// ---- trainable router on the matrix cores (bf16, E % 32 == 0, d % 64 == 0) ----------------
+// ---- trainable router on the matrix cores (bf16, E % 64 == 0, d % 64 == 0) ----------------
 // ws layout: [0,256) ticket counters; then dl as bf16 [T,E]; then the fp32 chunk sums [S,d,E].
 int router_dw_splits(int T, int d, int E) {
   const int tiles = ((d + BM - 1) / BM) * ((E + BN - 1) / BN);

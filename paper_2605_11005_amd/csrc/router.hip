@@ -2,7 +2,7 @@
 // gradient of the gate weights in one pass over dy), gradient through the gate weights to the
 // logits, and the router's backward GEMMs.
 //
-// Large bf16 shapes (E % 32 == 0, d % 64 == 0) run on the matrix cores through the grouped-GEMM
+// Large bf16 shapes (E % 64 == 0, d % 64 == 0) run on the matrix cores through the grouped-GEMM
 // kernel of expert_bf16.hip; every other shape (fp32, or a handful of experts) takes the plain
 // LDS-tiled FMA kernels below, which accept any size.  The contraction over the tokens (dWr) is
 // always split into fixed chunks whose fp32 sums are added in ascending order, so the result
@@ -397,7 +397,7 @@ int valu_splits(int T, int d, int E) {
 }
 
 inline bool mfma_shape(int dtype, int T, int d, int E) {
-  return dtype == MOE_BF16 && T > 0 && E % 32 == 0 && d % 64 == 0;
+  return dtype == MOE_BF16 && T > 0 && E % 64 == 0 && d % 64 == 0;
 }
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
