@@ -96,11 +96,15 @@ def main():
     # ---- timed region: exactly K steps, kernels bracketed by events inside the library
     B.moe_profile_enable(True)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t_start = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()     # asynchronous: per-step times for the min / median beside the bracketed mean
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     B.moe_profile_enable(False)
     ms_per_step = elapsed * 1e3 / args.steps
 
@@ -108,7 +112,8 @@ def main():
     for name in B.KERNEL_IDS:
         ms, n = B.moe_profile_read(name)
         if n:
-            kern[name] = dict(avg_ms=ms / n, launches=n)
+            lo, med = B.moe_profile_stats(name)
+            kern[name] = dict(avg_ms=ms / n, min_ms=lo, median_ms=med, launches=n)
     # enabling the profiler again starts a new log: the step's figures were read above
     router = None if args.no_router else router_row(B, C, W, torch, wl, dev, buf, R, U, b)
     chunked = {str(c): chunked_ms(torch, wl, dev, c, args.warmup, args.steps) for c in args.chunks}
@@ -166,7 +171,8 @@ def main():
 
     out = {
         "metric": "expert-layer fwd+bwd TFLOP/s", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_min": per_step[0], "ms_per_step_median": per_step[len(per_step) // 2], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "T": T, "d": d, "E": wl.E, "local_experts": wl.e_cnt, "k": k, "f": f,
                    "gate_mode": wl.gate_mode, "routed_rows_R": R, "tokens_with_local_slot_U": U,

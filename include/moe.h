@@ -228,6 +228,9 @@ int moe_router_bwd(const void* x, const void* wr, const float* dlogits, int dtyp
  *   moe_profile_read(kernel, &total_ms, &launches)
  *                            synchronises on the recorded events of that kernel (MOE_K_*)
  *                            and returns the summed elapsed time and the launch count.
+ *   moe_profile_stats(kernel, &min_ms, &median_ms)
+ *                            the shortest and the median launch of that kernel in the log
+ *                            (0 if it holds none); synchronises like moe_profile_read.
  * The pool holds MOE_PROFILE_MAX_EVENTS launches; later launches are not recorded.
  * Not thread-safe: enable, run and read from one host thread.
  */
@@ -237,6 +240,7 @@ enum { MOE_K_ROUTE = 0, MOE_K_PLAN = 1, MOE_K_DISPATCH = 2, MOE_K_COMBINE = 3, M
 #define MOE_PROFILE_MAX_EVENTS 8192
 int moe_profile_enable(int on);
 int moe_profile_read(int kernel, double* total_ms /* host */, int* launches /* host */);
+int moe_profile_stats(int kernel, double* min_ms /* host */, double* median_ms /* host */);
 
 /*
  * Measured ceilings, for benchmarks only (not part of the expert-layer path): the rates this

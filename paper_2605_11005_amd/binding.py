@@ -19,7 +19,7 @@ _LIB = None
 
 EXPORTS = ("moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
            "moe_router_fwd", "moe_combine_bwd", "moe_gate_bwd", "moe_router_bwd",
-           "moe_profile_enable", "moe_profile_read", "moe_probe_mfma_bf16", "moe_probe_copy",
+           "moe_profile_enable", "moe_profile_read", "moe_profile_stats", "moe_probe_mfma_bf16", "moe_probe_copy",
            "moe_workspace_bytes", "moe_error_string")
 
 
@@ -242,6 +242,16 @@ def moe_profile_read(kernel: str):
     ms, n = ctypes.c_double(0), ctypes.c_int(0)
     _check(lib.moe_profile_read(KERNEL_IDS[kernel], ctypes.byref(ms), ctypes.byref(n)), "moe_profile_read")
     return ms.value, n.value
+
+
+def moe_profile_stats(kernel: str):
+    """(shortest, median) launch in milliseconds of one kernel family since profiling was enabled."""
+    lib = load_library()
+    lib.moe_profile_stats.restype = ctypes.c_int
+    lib.moe_profile_stats.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lo, med = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib.moe_profile_stats(KERNEL_IDS[kernel], ctypes.byref(lo), ctypes.byref(med)), "moe_profile_stats")
+    return lo.value, med.value
 
 
 def moe_probe_mfma_bf16(sink, iters: int, random_operands: bool) -> float:

@@ -1,7 +1,9 @@
 // The C ABI (include/moe.h): argument validation on the host, then kernel launches.
 #include "kernels.h"
 
+#include <algorithm>
 #include <mutex>
+#include <vector>
 
 namespace {
 
@@ -88,6 +90,22 @@ int moe_profile_read(int kernel, double* total_ms, int* launches) {
   }
   *total_ms = sum;
   *launches = n;
+  return MOE_OK;
+}
+
+int moe_profile_stats(int kernel, double* min_ms, double* median_ms) {
+  if (kernel < 0 || kernel >= MOE_K_COUNT || !min_ms || !median_ms) return MOE_EINVAL;
+  std::vector<float> t;
+  for (int i = 0; i < g_prof.used; ++i) {
+    if (g_prof.kernel[i] != kernel) continue;
+    if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return MOE_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess) return MOE_EHIP;
+    t.push_back(ms);
+  }
+  std::sort(t.begin(), t.end());
+  *min_ms = t.empty() ? 0.0 : t.front();
+  *median_ms = t.empty() ? 0.0 : (t.size() % 2 ? t[t.size() / 2] : 0.5 * (t[t.size() / 2 - 1] + t[t.size() / 2]));
   return MOE_OK;
 }
 
