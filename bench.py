@@ -21,6 +21,7 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBPS = 8000.0
+INFINITY_CACHE_BYTES = 256 << 20
 
 # useful FLOP per routed row, in units of d*f, of each grouped-GEMM kernel
 GEMM_FLOP_UNITS = dict(up=4, down=2, da=2, dx=4, wg=2, wgd=4)
@@ -163,11 +164,15 @@ def main():
         roofline = dict(kernel="fp32 expert GEMMs (all)", bound="alu", achieved=fl / (ms_per_step * 1e-3) / 1e12,
                         peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s",
                         frac=fl / (ms_per_step * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, traffic=None)
+    # Within a step every mover launch touches other data than the one before it (x, then o, then dy,
+    # then dxp), so a launch re-reads nothing it left in a cache itself; but a launch whose bytes fit the
+    # 256 MB Infinity Cache may find its input there, written by the kernel before it: labelled.
     hbm = {}
-    for name in ("dispatch", "combine"):
+    for name, nbytes in (("dispatch", disp_bytes), ("combine", comb_bytes)):
         if name in kern:
             hbm[name] = dict(bound="hbm", achieved=kern[name]["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
-                             frac=kern[name]["GBps"] / HBM_PEAK_GBPS)
+                             frac=kern[name]["GBps"] / HBM_PEAK_GBPS, bytes_per_launch=nbytes,
+                             may_fit_infinity_cache=bool(nbytes < INFINITY_CACHE_BYTES))
 
     out = {
         "metric": "expert-layer fwd+bwd TFLOP/s", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
