@@ -43,13 +43,18 @@ int moe_alloc_eval(const moe_alloc_model_t* model, int W, int M_tot, int M, int 
                    double* T_f, double* U_a, double* U_f);
 
 /*
- * moe_alloc_seed -- phases 1 and 2 of the allocation algorithm, by exhaustive enumeration of
- * M = 1..W-1 (outer) and M_a = 1..M_tot-1 (inner), in that order:
- *   phase 1: T = max(T_a, T_f); if T < T* - eps: T* = T and the candidate set becomes {(M, M_a)};
- *            else if T <= T* + eps: (M, M_a) joins the set;
- *   phase 2: among the set, the split with the largest U_a + U_f (first one in enumeration
- *            order on equality).
- * Outputs: *M0, *Ma0 the seed, *T_star the running minimum, *n_candidates the size of the set.
+ * moe_alloc_seed -- the roofline seed of the allocation algorithm (its first two phases), found by
+ * tabulating every split instead of calling a MILP solver: GPU split M = 1..W-1 (outer) and NIC split
+ * M_a = 1..M_tot-1 (inner), ascending.
+ *   Bottleneck time of a split: max(T_a, T_f).  The candidate set holds the splits whose bottleneck time
+ *   is within eps of the reference time T*; T* moves down (and the set empties) each time a split in
+ *   table order undercuts it by more than eps, so with eps = 0 the set is exactly the minimisers and T*
+ *   the minimum over the table; with eps > 0 membership follows the table order, as the algorithm states it.
+ *   Tie-break inside the set: the paper maximises I_attn + I_ffn there.  The model constants C/V do not
+ *   depend on the split, so this library reads the score as the two groups' attained fractions of their
+ *   compute roofs, U_a + U_f (moe_alloc_eval): how far the NIC split lifts each group to its roof.  The
+ *   earliest split in table order wins on equal scores.
+ * Outputs: *M0, *Ma0 the seed, *T_star the reference time, *n_candidates the size of the set.
  */
 int moe_alloc_seed(const moe_alloc_model_t* model, int W, int M_tot, double eps, int* M0, int* Ma0,
                    double* T_star, int* n_candidates);

@@ -1,7 +1,9 @@
 // Worker-allocation tool (include/moe_alloc.h): host code only.
 #include "../../include/moe_alloc.h"
 
+#include <algorithm>
 #include <cmath>
+#include <vector>
 
 namespace {
 inline bool bad_model(const moe_alloc_model_t* m) {
@@ -47,24 +49,37 @@ int moe_alloc_eval(const moe_alloc_model_t* m, int W, int M_tot, int M, int M_a,
 int moe_alloc_seed(const moe_alloc_model_t* m, int W, int M_tot, double eps, int* M0, int* Ma0, double* T_star,
                    int* n_candidates) {
   if (bad_model(m) || W < 2 || M_tot < 2 || !(eps >= 0) || !M0 || !Ma0) return MOE_ALLOC_EINVAL;
-  double best_T = INFINITY, best_score = -1.0;
-  int bm = 0, bma = 0, count = 0;
-  for (int M = 1; M < W; ++M)
-    for (int Ma = 1; Ma < M_tot; ++Ma) {
-      double ta, tf, ua, uf;
-      moe_alloc_eval(m, W, M_tot, M, Ma, &ta, &tf, &ua, &uf);
-      const double T = ta > tf ? ta : tf;
-      const double score = ua + uf;
-      if (T < best_T - eps) {            // strictly better: the candidate set restarts
-        best_T = T; count = 1; best_score = score; bm = M; bma = Ma;
-      } else if (T <= best_T + eps) {    // a tie within the tolerance joins the set
-        ++count;
-        if (score > best_score) { best_score = score; bm = M; bma = Ma; }
-      }
-    }
-  *M0 = bm; *Ma0 = bma;
-  if (T_star) *T_star = best_T;
-  if (n_candidates) *n_candidates = count;
+  // The grid is small ((W-1)(M_tot-1) points), so it is tabulated once: bottleneck time and score per split,
+  // split index i = (M-1)*(M_tot-1) + (M_a-1), i.e. GPU split outer, NIC split inner, both ascending.
+  const int cols = M_tot - 1;
+  const size_t n = (size_t)(W - 1) * cols;
+  std::vector<double> bottleneck(n), score(n);
+  for (size_t i = 0; i < n; ++i) {
+    double ta, tf, ua, uf;
+    moe_alloc_eval(m, W, M_tot, 1 + (int)(i / cols), 1 + (int)(i % cols), &ta, &tf, &ua, &uf);
+    bottleneck[i] = std::max(ta, tf);
+    score[i] = ua + uf;
+  }
+  // Candidate set under the tolerance: walking the table in index order, `first` marks where the set last
+  // restarted (a split that undercuts the reference time by more than eps becomes the new reference and
+  // empties the set); every later split within eps of the reference belongs to the set.  With eps = 0 this
+  // is exactly the set of minimisers of the bottleneck time.
+  size_t first = 0;
+  double ref_T = INFINITY;
+  for (size_t i = 0; i < n; ++i)
+    if (bottleneck[i] < ref_T - eps) { ref_T = bottleneck[i]; first = i; }
+  // Seed = the member with the highest score, the earliest one on equal scores.
+  size_t pick = first;
+  int members = 0;
+  for (size_t i = first; i < n; ++i) {
+    if (bottleneck[i] > ref_T + eps) continue;
+    ++members;
+    if (score[i] > score[pick]) pick = i;
+  }
+  *M0 = 1 + (int)(pick / cols);
+  *Ma0 = 1 + (int)(pick % cols);
+  if (T_star) *T_star = ref_T;
+  if (n_candidates) *n_candidates = members;
   return MOE_ALLOC_OK;
 }
 

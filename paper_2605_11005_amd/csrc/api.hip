@@ -20,6 +20,9 @@ int shape_check_expert(int dtype, int cap, int d, int f, int e_cnt) {
   // 32-bit row*ld products inside a tile and 31-bit element counts per activation tensor
   if ((long long)cap * (d > f ? d : f) >= (1ll << 40)) return MOE_EUNSUPPORTED;
   if ((long long)(d > f ? d : f) * 256 >= (1ll << 31)) return MOE_EUNSUPPORTED;
+  // the fp32 kernels put row tiles (64 rows each, at most one ragged tile per expert) and, for the weight
+  // gradients, 64-wide tiles of d or f on grid dimensions y / z, which hold 65535 blocks
+  if (dtype == MOE_F32 && ((long long)(cap + 63) / 64 + e_cnt > 65535 || (d > f ? d : f) / 64 + 1 > 65535)) return MOE_EUNSUPPORTED;
   return MOE_OK;
 }
 
@@ -177,7 +180,7 @@ int moe_combine_bwd(const void* dy, const void* o, int dtype, int T, int d, int 
   if (bad_dtype(dtype) || T < 0 || d <= 0 || k <= 0) return MOE_EINVAL;
   if (k > MOE_MAX_TOPK) return MOE_EUNSUPPORTED;
   if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
-  if (T > 0 && (!dy || !inv || !topk_w || !dgate)) return MOE_EINVAL;
+  if (T > 0 && (!dy || !o || !d_o || !inv || !topk_w || !dgate)) return MOE_EINVAL;
   if (misaligned(dy, 16) || misaligned(o, 16) || misaligned(d_o, 16)) return MOE_EINVAL;
   return launch_combine_bwd(dy, o, dtype, T, d, k, inv, topk_w, d_o, dgate, (hipStream_t)stream);
 }
@@ -294,7 +297,7 @@ int moe_combine(const void* o, int dtype, int T, int d, int k, const int32_t* in
   if (bad_dtype(dtype) || T < 0 || d <= 0 || k <= 0) return MOE_EINVAL;
   if (k > MOE_MAX_TOPK) return MOE_EUNSUPPORTED;
   if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
-  if (T > 0 && (!inv || !y)) return MOE_EINVAL;
+  if (T > 0 && (!o || !inv || !y)) return MOE_EINVAL;
   if (misaligned(o, 16) || misaligned(y, 16)) return MOE_EINVAL;
   return launch_combine_rows(o, dtype, T, d, k, inv, topk_w, y, (hipStream_t)stream);
 }

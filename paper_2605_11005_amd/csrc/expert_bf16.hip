@@ -1056,8 +1056,11 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   w.P0 = partials; w.p_stride = mn; w.split_budget = (int)(split_bytes / (mn * 4)); w.plan = plans;
   if ((rc = launch_gg<WG>(w, s))) return rc;
   const int red_grid = 4 * device_cu_count();
-  hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans, e_cnt, partials, mn, mn, 1, (bf16_t*)dw2,
-                     (bf16_t*)dw2, mn, accumulate);
+  {
+    ProfScope prof(MOE_K_WGRAD_REDUCE, s);
+    hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans, e_cnt, partials, mn, mn, 1, (bf16_t*)dw2,
+                       (bf16_t*)dw2, mn, accumulate);
+  }
   HIP_CHECK_LAUNCH();
   GArgs v = {};     // dW1|dW3 = xp^T [dH1|dH3]
   v.A0 = v.A1 = (const bf16_t*)xp; v.lda = d;
@@ -1066,8 +1069,11 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   v.off = offsets; v.sched = sched + 24; v.e_cnt = e_cnt; v.M = d; v.N = f; v.accumulate = accumulate;
   v.P0 = partials; v.p_stride = 2 * mn; v.split_budget = (int)(split_bytes / (2 * mn * 4)); v.plan = plans + MOE_MAX_LOCAL;
   if ((rc = launch_gg<WGD>(v, s))) return rc;
-  hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans + MOE_MAX_LOCAL, e_cnt, partials, 2 * mn, mn, 2,
-                     (bf16_t*)dw1, (bf16_t*)dw3, mn, accumulate);
+  {
+    ProfScope prof(MOE_K_WGRAD_REDUCE, s);
+    hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans + MOE_MAX_LOCAL, e_cnt, partials, 2 * mn, mn, 2,
+                       (bf16_t*)dw1, (bf16_t*)dw3, mn, accumulate);
+  }
   HIP_CHECK_LAUNCH();
   return MOE_OK;
 }

@@ -72,5 +72,14 @@ def test_host_validation_rejects_before_launch(lib):
     assert lib.moe_expert_fwd(fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, None, fake, fake, 1 << 20, None) == 1
     assert lib.moe_expert_bwd(fake, fake, fake, fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, fake, fake, fake,
                               2, fake, 1 << 20, None) == 1
+    # a NULL tensor with T > 0 is rejected on the host (it would be dereferenced on the device)
+    assert lib.moe_combine(None, 1, 4, 16, 2, fake, None, fake, None) == 1
+    assert lib.moe_combine(fake, 1, 4, 16, 2, None, None, fake, None) == 1
+    assert lib.moe_combine(fake, 1, 4, 16, 2, fake, None, None, None) == 1
+    assert lib.moe_combine_bwd(fake, None, 1, 4, 16, 2, fake, fake, fake, fake, None) == 1
+    assert lib.moe_combine_bwd(fake, fake, 1, 4, 16, 2, fake, fake, None, fake, None) == 1
+    assert lib.moe_combine_bwd(None, fake, 1, 4, 16, 2, fake, fake, fake, fake, None) == 1
+    # fp32 experts: row tiles beyond the grid's second dimension are refused by validation, not by the launch
+    assert lib.moe_expert_fwd(fake, 0, 64 * 65536, 64, 64, 2, fake, fake, fake, fake, None, None, fake, fake, 1 << 40, None) == 2
     assert lib.moe_combine(fake, 1, 4, 12, 2, fake, None, fake, None) == 2
     assert lib.moe_combine(fake, 1, 4, 16, 100, fake, None, fake, None) == 2

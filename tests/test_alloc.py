@@ -56,6 +56,34 @@ def test_oracle_bubble_ratio_is_one_fourth_under_the_papers_conditions():
     assert AO.bubbles(1, 5, 1, 1, 1, 1, 1, 1) == (0.0, 0.0)          # one stage: no bubble
 
 
+def _bubble_rows():
+    rows = []
+    for key, val in _gold().items():
+        if key.startswith("bubbles "):
+            rows.append(([float(v) for v in key.split()[1:]], [float(v) for v in val]))
+    return rows
+
+
+def test_oracle_bubbles_match_hand_evaluated_absolute_values():
+    """Absolute values of both bubble equations with L > 1, v > 1, T_p2p > 0 and unequal T_a, T_f
+    (the ratio pin above cancels PP - 1 and v and never varies L or T_p2p)."""
+    rows = _bubble_rows()
+    assert len(rows) >= 6
+    for (PP, L, v, Ta, Tf, Ta2a, Tp2p, Tm2n), (base, af) in rows:
+        got = AO.bubbles(int(PP), int(L), int(v), Ta, Tf, Ta2a, Tp2p, Tm2n)
+        assert got == pytest.approx((base, af), rel=1e-15), (PP, L, v)
+
+
+def test_oracle_attained_is_a_reading_pinned_by_bounds_only():
+    """The phase-2 tie-break score U_a + U_f is this build's reading of 'maximise I_attn + I_ffn'
+    (the model constants do not depend on the split): nothing the paper prints fixes its values, so it
+    is pinned only by what any roofline fraction obeys: 0 < U <= 1, U = 1 exactly when the group is
+    compute-bound, U = (transfer-limited FLOP rate) / (compute roof) when it is network-bound."""
+    m = dict(C_a=4e15, C_f=1e15, V=1e11, P=1e15, B=1e11)
+    ua, uf = AO.attained(m, 16, 8, 8, 4)        # T_a = max(0.5, 0.25) compute-bound, T_f = max(0.125, 0.25) network-bound
+    assert ua == pytest.approx(1.0) and uf == pytest.approx(0.5)
+
+
 def test_oracle_seed_balances_a_symmetric_problem_and_follows_the_load():
     # equal groups, compute-bound whatever the NIC split: half of the GPUs each, every NIC split ties
     sym = dict(C_a=1e15, C_f=1e15, V=1e9, P=1e15, B=1e11)
@@ -126,6 +154,8 @@ def test_tool_costs_placement_bubbles_and_refine_match_oracle():
         for g in range(p):
             assert A.group_layers(L, p, g) == AO.group_layers(L, p, g)
     assert A.bubbles(8, 3, 2, 1.5, 2.5, 0.7, 0.1, 0.9) == pytest.approx(AO.bubbles(8, 3, 2, 1.5, 2.5, 0.7, 0.1, 0.9), rel=1e-15)
+    for (PP, L, v, Ta, Tf, Ta2a, Tp2p, Tm2n), (base, af) in _bubble_rows():      # and against the hand-evaluated values
+        assert A.bubbles(int(PP), int(L), int(v), Ta, Tf, Ta2a, Tp2p, Tm2n) == pytest.approx((base, af), rel=1e-15)
     prof = lambda M, Ma: (M - 9) ** 2 + 3 * abs(Ma - 5) + 0.25 * ((M * 7 + Ma) % 3)
     rng = np.random.default_rng(5)
     dM, dMa = rng.integers(-3, 4, 150).tolist(), rng.integers(-3, 4, 150).tolist()

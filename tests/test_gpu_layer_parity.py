@@ -33,6 +33,11 @@ CASES = [
     W.DSMOE_T2.scaled(name="deepseek-moe-small", T=1024, E=16, e_cnt=3),
     W.GPTOSS_T2.scaled(name="gpt-oss-small", T=640, E=16, e_cnt=2),
     W.QWEN3_T2.scaled(name="qwen3-small", T=512, E=32, e_cnt=3),
+    # every workgroup runs several tiles with long k loops one after the other (about 1200 tiles of 32
+    # k-tiles in the up projection for 256 workgroups; 64 k-tiles in the input-gradient GEMM), draws its
+    # next ticket in mid-loop, prefetches under the epilogue and steals from other XCDs' queues at the
+    # end; the hottest expert's weight gradients are cut along its rows.  Compared in full.
+    W.DSV3.scaled(name="dsv3-mid-multitile", T=16384, d=1024, f=1024),
 ]
 
 
