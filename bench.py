@@ -39,6 +39,11 @@ def main():
     ap.add_argument("--chunks", type=int, nargs="*", default=[],
                     help="also time the token-chunked two-stream schedule with these chunk counts (reported beside "
                          "the headline value, not inside it)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the compact records of the other configurations (default run of the headline workload only)")
+    ap.add_argument("--other-steps", type=int, default=5, help="timed steps per workload of the other_workloads block")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the MFMA-only / copy / vendor-GEMM ceiling kernels (counter runs that only need the step)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run three plain 1 GiB device copies (a kernel of known HBM "
                          "traffic) so that a rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE run can be scaled")
@@ -48,6 +53,33 @@ def main():
               "(no collectives or multi-GPU sharding are part of it)", file=sys.stderr)
         sys.exit(2)
 
+    import torch
+    from paper_2605_11005_amd import binding as B
+    from paper_2605_11005_amd import workloads as W
+
+    wl = W.BY_NAME[args.workload]
+    B.load_library()
+    torch.cuda.set_device(0)
+    out, host_inputs = run_workload(wl, args.steps, args.warmup, full=True, args=args)
+
+    if not args.no_other_workloads and args.workload == "dsv3-like-share":
+        # The remaining headline configurations and the paper's model-table shapes, after the headline's
+        # timed region: whole-step rate, step time and the slowest grouped-GEMM kernel of each.
+        others = {}
+        for w in [W.MIXTRAL, W.QWEN, W.SKEW] + W.MODEL_TABLE:
+            r, _ = run_workload(w, args.other_steps, 2, full=False, args=args)
+            others[w.name] = r
+        out["other_workloads"] = others
+
+    if not args.no_cpu_baseline:
+        x, logits, dy = host_inputs
+        out["cpu_baseline"] = cpu_baseline(wl, x, logits, dy, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+def run_workload(wl, steps, warmup, full, args):
+    """K timed steps of the whole hot path on one workload.  full=True: the complete record of the
+    headline line; full=False: the compact record of the `other_workloads` block."""
     import numpy as np
     import torch
     from paper_2605_11005_amd import binding as B
@@ -55,12 +87,8 @@ def main():
     from paper_2605_11005_amd import workloads as W
     from paper_2605_11005_amd.layer import MoeLayerBuffers, run_backward, run_forward, to_device, torch_dtype
 
-    wl = W.BY_NAME[args.workload]
     bf16 = wl.dtype == "bf16"
     b = 2 if bf16 else 4
-    B.load_library()
-    torch.cuda.set_device(0)
-
     t0 = time.time()
     x = W.tokens(wl)
     logits = W.router_logits(wl, x)
@@ -81,7 +109,7 @@ def main():
     R = int(counts.sum())
     local = ((ti >= wl.e_lo) & (ti < wl.e_lo + wl.e_cnt))
     U = int(local.any(dim=1).sum().item())
-    del ti, tw, cnt
+    del ti, tw, cnt, local
     cap = max(R, 1)
     buf = MoeLayerBuffers(wl, cap=cap)
 
@@ -89,7 +117,7 @@ def main():
         run_forward(wl, dev, buf)
         run_backward(wl, dev, buf)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     assert buf.status() == 0
@@ -97,17 +125,17 @@ def main():
     # ---- timed region: exactly K steps, kernels bracketed by events inside the library
     B.moe_profile_enable(True)
     torch.cuda.synchronize()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t_start = time.perf_counter()
     marks[0].record()
-    for i in range(args.steps):
+    for i in range(steps):
         step()
         marks[i + 1].record()     # asynchronous: per-step times for the min / median beside the bracketed mean
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     B.moe_profile_enable(False)
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step = elapsed * 1e3 / steps
 
     kern = {}
     for name in B.KERNEL_IDS:
@@ -115,24 +143,12 @@ def main():
         if n:
             lo, med = B.moe_profile_stats(name)
             kern[name] = dict(avg_ms=ms / n, min_ms=lo, median_ms=med, launches=n)
-    # enabling the profiler again starts a new log: the step's figures were read above
-    router = None if args.no_router else router_row(B, C, W, torch, wl, dev, buf, R, U, b)
-    chunked = {str(c): chunked_ms(torch, wl, dev, c, args.warmup, args.steps) for c in args.chunks}
-    ceilings = measured_ceilings(B, torch)
-
-    if args.calibration_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     d, f, T, k = wl.d, wl.f, wl.T, wl.k
     flop_step = C.layer_flops(R, d, f)
     value = flop_step / (ms_per_step * 1e-3) / 1e12
-
-    gemm_ms = sum(kern[n]["avg_ms"] * kern[n]["launches"] for n in GEMM_FLOP_UNITS if n in kern) / args.steps
+    # per step: the six grouped-GEMM launches plus the two partial-tile reductions of cut weight gradients
+    gemm_ms = sum(kern[n]["avg_ms"] * kern[n]["launches"] for n in list(GEMM_FLOP_UNITS) + ["wgrad_reduce"] if n in kern) / steps
     for name, units in GEMM_FLOP_UNITS.items():
         if name in kern:
             kern[name]["tflops"] = C.gemm_flops(R, d, f, units / 2) / (kern[name]["avg_ms"] * 1e-3) / 1e12
@@ -173,15 +189,41 @@ def main():
             hbm[name] = dict(bound="hbm", achieved=kern[name]["GBps"], peak=HBM_PEAK_GBPS, unit="GB/s",
                              frac=kern[name]["GBps"] / HBM_PEAK_GBPS, bytes_per_launch=nbytes,
                              may_fit_infinity_cache=bool(nbytes < INFINITY_CACHE_BYTES))
+    config = {"workload": wl.name, "T": T, "d": d, "E": wl.E, "local_experts": wl.e_cnt, "k": k, "f": f,
+              "gate_mode": wl.gate_mode, "routed_rows_R": R, "tokens_with_local_slot_U": U,
+              "rows_per_expert_min_max": [int(counts.min()), int(counts.max())]}
+    if not full:
+        rec = {"value": value, "unit": "TFLOP/s", "ms_per_step": ms_per_step, "steps": steps, "dtype": wl.dtype,
+               "config": config,
+               "dominant_kernel": {"kernel": roofline["kernel"], "achieved": roofline["achieved"], "frac": roofline["frac"]},
+               "all_gemms_tflops": roofline.get("all_gemms_tflops"),
+               "all_gemms_frac_of_composite_bound": roofline.get("all_gemms_frac_of_composite_bound"),
+               "dispatch_combine_GBps": [hbm.get("dispatch", {}).get("achieved"), hbm.get("combine", {}).get("achieved")],
+               "dispatch_combine_may_fit_infinity_cache": [hbm.get("dispatch", {}).get("may_fit_infinity_cache"),
+                                                           hbm.get("combine", {}).get("may_fit_infinity_cache")]}
+        del dev, buf
+        torch.cuda.empty_cache()
+        return rec, None
+
+    # enabling the profiler again starts a new log: the step's figures were read above
+    router = None if args.no_router else router_row(B, C, W, torch, wl, dev, buf, R, U, b)
+    chunked = {str(c): chunked_ms(torch, wl, dev, c, warmup, steps) for c in args.chunks}
+    ceilings = None if args.no_ceilings else measured_ceilings(B, torch)
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = {
         "metric": "expert-layer fwd+bwd TFLOP/s", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "ms_per_step_min": per_step[0], "ms_per_step_median": per_step[len(per_step) // 2], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "T": T, "d": d, "E": wl.E, "local_experts": wl.e_cnt, "k": k, "f": f,
-                   "gate_mode": wl.gate_mode, "routed_rows_R": R, "tokens_with_local_slot_U": U,
-                   "rows_per_expert_min_max": [int(counts.min()), int(counts.max())]},
+        "config": config,
         "roofline": roofline, "hbm_kernels": hbm, "measured_ceilings": ceilings, "kernels": kern,
         "dispatch_combine_GBps": [hbm.get("dispatch", {}).get("achieved"), hbm.get("combine", {}).get("achieved")],
         "input_generation_s": gen_s,
@@ -190,10 +232,9 @@ def main():
         out["trainable_gate"] = router
     if chunked:
         out["chunked_schedule_ms_per_step"] = chunked
-
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, x, logits, dy, args.cpu_seconds)
-    print(json.dumps(out))
+    del dev, buf
+    torch.cuda.empty_cache()
+    return out, (x, logits, dy)
 
 
 def router_row(B, C, W, torch, wl, dev, buf, R, U, b, reps=10):
