@@ -230,6 +230,7 @@ int moe_dispatch(const void* x, int dtype, int T, int d, int k, const int32_t* t
   if (k > MOE_MAX_TOPK || e_cnt > MOE_MAX_LOCAL) return MOE_EUNSUPPORTED;
   if ((long long)T * k >= (1ll << 31)) return MOE_EUNSUPPORTED;
   if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
+  if ((long long)T * ((d / (dtype == MOE_BF16 ? 8 : 4) + 127) / 128) >= (1ll << 31)) return MOE_EUNSUPPORTED;   // mover grid
   if (!offsets) return MOE_EINVAL;
   if (T > 0 && (!x || !inv)) return MOE_EINVAL;
   if (cap > 0 && (!xp || !perm)) return MOE_EINVAL;
@@ -297,6 +298,7 @@ int moe_combine(const void* o, int dtype, int T, int d, int k, const int32_t* in
   if (bad_dtype(dtype) || T < 0 || d <= 0 || k <= 0) return MOE_EINVAL;
   if (k > MOE_MAX_TOPK) return MOE_EUNSUPPORTED;
   if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
+  if ((long long)T * ((d / (dtype == MOE_BF16 ? 8 : 4) + 127) / 128) >= (1ll << 31)) return MOE_EUNSUPPORTED;   // mover grid
   if (T > 0 && (!o || !inv || !y)) return MOE_EINVAL;
   if (misaligned(o, 16) || misaligned(y, 16)) return MOE_EINVAL;
   return launch_combine_rows(o, dtype, T, d, k, inv, topk_w, y, (hipStream_t)stream);

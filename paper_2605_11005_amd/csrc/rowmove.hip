@@ -5,8 +5,10 @@
 //              of the token's local rows            -> (U + R) * d * b bytes
 //   combine  : read the token's local rows, write y[t] once (zeros when none)
 //                                                   -> (R + T) * d * b bytes
-// Accesses are 16 bytes per lane and one vector per thread (grid = row segments x tokens):
-// on this chip a plain copy is fastest with the largest possible number of small threads.
+// Accesses are 16 bytes per lane and one vector per thread: on this chip a plain copy is fastest
+// with the largest possible number of small threads.  Dispatch numbers its blocks row-segment
+// fastest, token next, so that blocks resident together work on consecutive 2 KB pieces of the
+// same rows (source and destinations): DRAM pages are used while they are open.
 #include "common.h"
 #include "kernels.h"
 
@@ -33,20 +35,21 @@ __device__ __forceinline__ u32x4 scale_vec(u32x4 v, float sc) {
   }
 }
 
-// row_vecs = number of 16-byte vectors per row.  grid = (tokens, row segments of blockDim.x vectors);
-// one vector per thread: the copy is fastest with many small independent threads.
-// Block sizes are set at launch: dispatch (write-heavy) is fastest with 256-thread blocks,
-// combine (read-heavy gather) with one block per token row (up to 1024 threads).
-constexpr int DISPATCH_BLOCK = 256;
-constexpr int COMBINE_BLOCK_MAX = 1024;
+// row_vecs = number of 16-byte vectors per row; one vector per thread.
+// dispatch: 1-D grid of T * n_seg blocks of 128 threads, block = (token t, segment of 128 vectors),
+//   segment fastest.  Measured at T = 32768, d = 7168 (896 vectors = 7 segments): 6.3 TB/s against
+//   5.4 TB/s with the token index fastest and 256-thread blocks (whose fourth block is half empty).
+// combine: the same numbering and block size (6.5 TB/s against 6.1-6.3 TB/s with one block per token row).
+constexpr int DISPATCH_BLOCK = 128;
+constexpr int COMBINE_BLOCK = 128;
 
 template <bool BF16, bool SCALED>
-__global__ __launch_bounds__(DISPATCH_BLOCK) void dispatch_rows(const u32x4* __restrict__ x, int T, int row_vecs, int k,
-                                                    const int32_t* __restrict__ inv,
+__global__ __launch_bounds__(DISPATCH_BLOCK) void dispatch_rows(const u32x4* __restrict__ x, int T, int row_vecs, int n_seg,
+                                                    int k, const int32_t* __restrict__ inv,
                                                     const float* __restrict__ row_scale,
                                                     u32x4* __restrict__ xp) {
-  const int t = blockIdx.x;
-  const int c = blockIdx.y * blockDim.x + threadIdx.x;
+  const int t = blockIdx.x / n_seg;
+  const int c = (blockIdx.x - t * n_seg) * DISPATCH_BLOCK + threadIdx.x;
   const int32_t* irow = inv + (size_t)t * k;         // uniform address: scalar loads
   int first = -1;
   for (int j = 0; j < k; ++j)
@@ -89,12 +92,12 @@ __device__ __forceinline__ u32x4 pack_acc(const float* acc) {
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(COMBINE_BLOCK_MAX) void combine_rows(const u32x4* __restrict__ o, int T, int row_vecs, int k,
-                                                   const int32_t* __restrict__ inv,
+__global__ __launch_bounds__(COMBINE_BLOCK) void combine_rows(const u32x4* __restrict__ o, int T, int row_vecs, int n_seg,
+                                                   int k, const int32_t* __restrict__ inv,
                                                    const float* __restrict__ topk_w,
                                                    u32x4* __restrict__ y) {
-  const int t = blockIdx.x;
-  const int c = blockIdx.y * blockDim.x + threadIdx.x;
+  const int t = blockIdx.x / n_seg;
+  const int c = (blockIdx.x - t * n_seg) * COMBINE_BLOCK + threadIdx.x;
   if (c >= row_vecs) return;
   const int32_t* irow = inv + (size_t)t * k;         // uniform address: scalar loads
   float acc[8];
@@ -117,15 +120,17 @@ int launch_dispatch_rows(const void* x, int dtype, int T, int d, int k, const in
   if (T == 0) return MOE_OK;
   ProfScope prof(MOE_K_DISPATCH, s);
   const int row_vecs = dtype == MOE_BF16 ? d / 8 : d / 4;
-  dim3 grid(T, (row_vecs + DISPATCH_BLOCK - 1) / DISPATCH_BLOCK), block(DISPATCH_BLOCK);
+  const int n_seg = (row_vecs + DISPATCH_BLOCK - 1) / DISPATCH_BLOCK;
+  if ((long long)T * n_seg >= (1ll << 31)) return MOE_EUNSUPPORTED;      // 1-D grid limit (checked by the entry point too)
+  dim3 grid((unsigned)(T * n_seg)), block(DISPATCH_BLOCK);
   const u32x4* xs = (const u32x4*)x;
   u32x4* xd = (u32x4*)xp;
   if (dtype == MOE_BF16) {
-    if (row_scale) hipLaunchKernelGGL((dispatch_rows<true, true>), grid, block, 0, s, xs, T, row_vecs, k, inv, row_scale, xd);
-    else hipLaunchKernelGGL((dispatch_rows<true, false>), grid, block, 0, s, xs, T, row_vecs, k, inv, row_scale, xd);
+    if (row_scale) hipLaunchKernelGGL((dispatch_rows<true, true>), grid, block, 0, s, xs, T, row_vecs, n_seg, k, inv, row_scale, xd);
+    else hipLaunchKernelGGL((dispatch_rows<true, false>), grid, block, 0, s, xs, T, row_vecs, n_seg, k, inv, row_scale, xd);
   } else {
-    if (row_scale) hipLaunchKernelGGL((dispatch_rows<false, true>), grid, block, 0, s, xs, T, row_vecs, k, inv, row_scale, xd);
-    else hipLaunchKernelGGL((dispatch_rows<false, false>), grid, block, 0, s, xs, T, row_vecs, k, inv, row_scale, xd);
+    if (row_scale) hipLaunchKernelGGL((dispatch_rows<false, true>), grid, block, 0, s, xs, T, row_vecs, n_seg, k, inv, row_scale, xd);
+    else hipLaunchKernelGGL((dispatch_rows<false, false>), grid, block, 0, s, xs, T, row_vecs, n_seg, k, inv, row_scale, xd);
   }
   HIP_CHECK_LAUNCH();
   return MOE_OK;
@@ -136,13 +141,13 @@ int launch_combine_rows(const void* o, int dtype, int T, int d, int k, const int
   if (T == 0) return MOE_OK;
   ProfScope prof(MOE_K_COMBINE, s);
   const int row_vecs = dtype == MOE_BF16 ? d / 8 : d / 4;
-  int bs = (row_vecs + WAVE - 1) / WAVE * WAVE;
-  if (bs > COMBINE_BLOCK_MAX) bs = COMBINE_BLOCK_MAX;
-  dim3 grid(T, (row_vecs + bs - 1) / bs), block(bs);
+  const int n_seg = (row_vecs + COMBINE_BLOCK - 1) / COMBINE_BLOCK;
+  if ((long long)T * n_seg >= (1ll << 31)) return MOE_EUNSUPPORTED;      // 1-D grid limit (checked by the entry point too)
+  dim3 grid((unsigned)(T * n_seg)), block(COMBINE_BLOCK);
   if (dtype == MOE_BF16)
-    hipLaunchKernelGGL((combine_rows<true>), grid, block, 0, s, (const u32x4*)o, T, row_vecs, k, inv, topk_w, (u32x4*)y);
+    hipLaunchKernelGGL((combine_rows<true>), grid, block, 0, s, (const u32x4*)o, T, row_vecs, n_seg, k, inv, topk_w, (u32x4*)y);
   else
-    hipLaunchKernelGGL((combine_rows<false>), grid, block, 0, s, (const u32x4*)o, T, row_vecs, k, inv, topk_w, (u32x4*)y);
+    hipLaunchKernelGGL((combine_rows<false>), grid, block, 0, s, (const u32x4*)o, T, row_vecs, n_seg, k, inv, topk_w, (u32x4*)y);
   HIP_CHECK_LAUNCH();
   return MOE_OK;
 }
