@@ -103,6 +103,28 @@ int moe_dispatch(const void* x, int dtype, int T, int d, int k, const int32_t* t
                  moe_stream_t stream);
 
 /*
+ * moe_dispatch_static -- moe_dispatch (plan + row move, reuse_plan == 0) for callers that cannot
+ * allocate device memory or pass a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The plan's scratch (its per-chunk histogram table and the
+ * expert bases) lives in a MOE_STATIC_PLAN_BYTES array inside the library's code object; each GPU
+ * that runs the library holds its own copy until the process ends.  The call allocates nothing
+ * and frees nothing.  Outputs are bit-identical to moe_dispatch's.
+ *   arguments as moe_dispatch, without reuse_plan / ws / ws_bytes, plus
+ *   status   int32 (device) out, may be NULL: 1 if R > cap (rows dropped as in moe_dispatch), else 0.
+ * Limit: the plan tables must fit the array, 256 + 4 (ceil(T k / 512) e_cnt + e_cnt + 1) <=
+ * MOE_STATIC_PLAN_BYTES (at e_cnt = 32 that is T k <= 16.7 million slots); beyond it the call
+ * returns MOE_EWORKSPACE and enqueues nothing.  Other errors as moe_dispatch.
+ * The array is shared by every call on a GPU and keeps the last call's contents (each call
+ * overwrites what it reads, nothing needs clearing): calls that overlap on one GPU, on different
+ * streams or from different threads, race; serialise them.  The first call on a device looks up
+ * the array's device address (no allocation); make it before a graph capture starts.
+ */
+#define MOE_STATIC_PLAN_BYTES (4 << 20)
+int moe_dispatch_static(const void* x, int dtype, int T, int d, int k, const int32_t* topk_idx,
+                        const float* row_scale, int e_lo, int e_cnt, int32_t* offsets, int32_t* perm,
+                        int32_t* inv, void* xp, int cap, int32_t* status, moe_stream_t stream);
+
+/*
  * moe_expert_fwd -- the expert FFNs as grouped GEMMs over expert-contiguous rows
  * (resource-allocation section: after gating, GroupGEMMs over the k*S routed tokens).
  * For each local expert e and its rows [offsets[e], offsets[e+1]):

@@ -17,7 +17,7 @@ WS_DISPATCH, WS_EXPERT_FWD, WS_EXPERT_BWD, WS_ROUTER = 0, 1, 2, 3
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-EXPORTS = ("moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
+EXPORTS = ("moe_route", "moe_dispatch", "moe_dispatch_static", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
            "moe_router_fwd", "moe_combine_bwd", "moe_gate_bwd", "moe_router_bwd",
            "moe_profile_enable", "moe_profile_read", "moe_profile_stats", "moe_probe_mfma_bf16", "moe_probe_copy",
            "moe_workspace_bytes", "moe_error_string")
@@ -46,6 +46,9 @@ def load_library():
     lib.moe_dispatch.restype = c_int
     lib.moe_dispatch.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_int, c_int, c_void_p,
                                  c_void_p, c_void_p, c_int, c_void_p, c_int, c_void_p, c_size_t, c_void_p]
+    lib.moe_dispatch_static.restype = c_int
+    lib.moe_dispatch_static.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_int, c_int, c_void_p,
+                                        c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     lib.moe_expert_fwd.restype = c_int
     lib.moe_expert_fwd.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p,
                                    c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
@@ -137,6 +140,24 @@ def moe_dispatch(x, k, topk_idx, row_scale, e_lo, e_cnt, offsets, perm, inv, reu
                                        _ptr(offsets), _ptr(perm), _ptr(inv), int(reuse_plan), _ptr(xp), cap,
                                        _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream()),
            "moe_dispatch")
+
+
+def moe_dispatch_static(x, k, topk_idx, row_scale, e_lo, e_cnt, offsets, perm, inv, xp, status=None):
+    """moe_dispatch (plan + row move) on the library's built-in plan scratch: no workspace argument."""
+    import torch
+    T, d = x.shape
+    cap = xp.shape[0]
+    _need(x, name="x"); _need(xp, x.dtype, (cap, d), "xp")
+    _need(topk_idx, torch.int32, (T, k), "topk_idx")
+    _need(row_scale, torch.float32, (T, k), "row_scale")
+    _need(offsets, torch.int32, (e_cnt + 1,), "offsets")
+    _need(perm, torch.int32, (cap,), "perm")
+    _need(inv, torch.int32, (T, k), "inv")
+    _need(status, torch.int32, name="status")
+    lib = load_library()
+    _check(lib.moe_dispatch_static(_ptr(x), _dtype_code(x), T, d, k, _ptr(topk_idx), _ptr(row_scale), e_lo, e_cnt,
+                                   _ptr(offsets), _ptr(perm), _ptr(inv), _ptr(xp), cap, _ptr(status), _stream()),
+           "moe_dispatch_static")
 
 
 def moe_expert_fwd(xp, offsets, w1, w3, w2, h1, h3, o, ws):

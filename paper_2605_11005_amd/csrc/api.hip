@@ -239,9 +239,31 @@ int moe_dispatch(const void* x, int dtype, int T, int d, int k, const int32_t* t
   if (!reuse_plan) {
     if (T > 0 && !topk_idx) return MOE_EINVAL;
     if (!ws || misaligned(ws, 256) || ws_bytes < plan_ws_bytes(T, k, e_cnt)) return MOE_EWORKSPACE;
-    int rc = launch_plan(topk_idx, T, k, e_lo, e_cnt, offsets, perm, inv, cap, ws, s);
+    int rc = launch_plan(topk_idx, T, k, e_lo, e_cnt, offsets, perm, inv, cap, ws, nullptr, s);
     if (rc) return rc;
   }
+  return launch_dispatch_rows(x, dtype, T, d, k, inv, row_scale, xp, s);
+}
+
+int moe_dispatch_static(const void* x, int dtype, int T, int d, int k, const int32_t* topk_idx,
+                        const float* row_scale, int e_lo, int e_cnt, int32_t* offsets, int32_t* perm,
+                        int32_t* inv, void* xp, int cap, int32_t* status, moe_stream_t stream) {
+  if (bad_dtype(dtype) || T < 0 || d <= 0 || k <= 0 || e_lo < 0 || e_cnt < 0 || cap < 0) return MOE_EINVAL;
+  if (k > MOE_MAX_TOPK || e_cnt > MOE_MAX_LOCAL) return MOE_EUNSUPPORTED;
+  if ((long long)T * k >= (1ll << 31)) return MOE_EUNSUPPORTED;
+  if (dtype == MOE_BF16 ? d % 8 : d % 4) return MOE_EUNSUPPORTED;
+  if ((long long)T * ((d / (dtype == MOE_BF16 ? 8 : 4) + 127) / 128) >= (1ll << 31)) return MOE_EUNSUPPORTED;   // mover grid
+  if (!offsets) return MOE_EINVAL;
+  if (T > 0 && (!x || !inv || !topk_idx)) return MOE_EINVAL;
+  if (cap > 0 && (!xp || !perm)) return MOE_EINVAL;
+  if (misaligned(x, 16) || misaligned(xp, 16)) return MOE_EINVAL;
+  // the plan tables of this call must fit the built-in scratch
+  if (plan_ws_bytes(T, k, e_cnt) > (size_t)MOE_STATIC_PLAN_BYTES) return MOE_EWORKSPACE;
+  void* ws = nullptr;
+  int rc = plan_static_scratch(&ws);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  if ((rc = launch_plan(topk_idx, T, k, e_lo, e_cnt, offsets, perm, inv, cap, ws, status, s))) return rc;
   return launch_dispatch_rows(x, dtype, T, d, k, inv, row_scale, xp, s);
 }
 

@@ -10,8 +10,11 @@ int launch_route(const float* logits, int T, int E, int k, int gate_mode, int e_
                  int32_t* topk_idx, float* topk_w, int32_t* counts, hipStream_t s);
 
 size_t plan_ws_bytes(int T, int k, int e_cnt);
+// status_out: where the overflow status word goes (NULL: the first word of ws)
 int launch_plan(const int32_t* topk_idx, int T, int k, int e_lo, int e_cnt, int32_t* offsets,
-                int32_t* perm, int32_t* inv, int cap, void* ws, hipStream_t s);
+                int32_t* perm, int32_t* inv, int cap, void* ws, int32_t* status_out, hipStream_t s);
+// device address of this GPU's built-in plan scratch (MOE_STATIC_PLAN_BYTES bytes); looks it up on first use
+int plan_static_scratch(void** ptr);
 
 int launch_dispatch_rows(const void* x, int dtype, int T, int d, int k, const int32_t* inv,
                          const float* row_scale, void* xp, hipStream_t s);

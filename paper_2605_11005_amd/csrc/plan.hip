@@ -13,6 +13,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <mutex>
+
 namespace {
 
 constexpr int CHUNK = 512;   // slots per wavefront
@@ -130,6 +132,30 @@ __global__ __launch_bounds__(64) void plan_scatter(const int32_t* __restrict__ t
 
 }  // namespace
 
+// ---- plan scratch that lives in the code object, for callers that cannot allocate ---------
+// One array per GPU (each device that loads the library holds its own copy at its own address
+// until the process ends).  Host code never passes the array's name to a kernel: the name is a
+// host-side stand-in, the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_PLAN_BYTES];
+
+namespace {
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[64] = {};
+}  // namespace
+
+int plan_static_scratch(void** ptr) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_EHIP;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MOE_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return MOE_OK;
+}
+
 size_t plan_ws_bytes(int T, int k, int e_cnt) {
   size_t n_slots = (size_t)T * (size_t)k;
   size_t n_chunks = (n_slots + CHUNK - 1) / CHUNK;
@@ -138,9 +164,9 @@ size_t plan_ws_bytes(int T, int k, int e_cnt) {
 }
 
 int launch_plan(const int32_t* topk_idx, int T, int k, int e_lo, int e_cnt, int32_t* offsets,
-                int32_t* perm, int32_t* inv, int cap, void* ws, hipStream_t s) {
+                int32_t* perm, int32_t* inv, int cap, void* ws, int32_t* status_out, hipStream_t s) {
   ProfScope prof(MOE_K_PLAN, s);
-  int32_t* status = (int32_t*)ws;
+  int32_t* status = status_out ? status_out : (int32_t*)ws;
   int32_t* ws_hist = (int32_t*)((char*)ws + 256);
   const long long n_slots = (long long)T * k;
   const int n_chunks = (int)((n_slots + CHUNK - 1) / CHUNK);

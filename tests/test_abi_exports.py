@@ -82,4 +82,10 @@ def test_host_validation_rejects_before_launch(lib):
     # fp32 experts: row tiles beyond the grid's second dimension are refused by validation, not by the launch
     assert lib.moe_expert_fwd(fake, 0, 64 * 65536, 64, 64, 2, fake, fake, fake, fake, None, None, fake, fake, 1 << 40, None) == 2
     assert lib.moe_combine(fake, 1, 4, 12, 2, fake, None, fake, None) == 2
+    # the entry point without a workspace argument refuses plans larger than its built-in scratch:
+    # 2^22 tokens x top-8 over 1024 local experts need a 268 MB chunk table
+    assert lib.moe_dispatch_static(fake, 1, 1 << 22, 64, 8, fake, None, 0, 1024, fake, fake, fake, fake, 1 << 25, None, None) == 3
+    assert B.moe_workspace_bytes(B.WS_DISPATCH, B.MOE_BF16, 1 << 22, 8, 64, 64, 1024, 0) > (4 << 20)
+    assert lib.moe_dispatch_static(fake, 1, 4, 12, 2, fake, None, 0, 4, fake, fake, fake, fake, 8, None, None) == 2
+    assert lib.moe_dispatch_static(fake, 1, 4, 16, 2, None, None, 0, 4, fake, fake, fake, fake, 8, None, None) == 1
     assert lib.moe_combine(fake, 1, 4, 16, 100, fake, None, fake, None) == 2
