@@ -133,6 +133,9 @@ int moe_dispatch_static(const void* x, int dtype, int T, int d, int k, const int
  *
  *   xp [cap,d]; w1,w3 [e_cnt,d,f]; w2 [e_cnt,f,d] (local slice: index 0 = expert e_lo)
  *   h1,h3 [cap,f]  out, saved for the backward pass; both NULL = forward only
+ *   a  [cap,f]     out, may be NULL: the activation silu(h1) * h3 as the down projection consumed it
+ *                  (rounded to dtype).  A caller that keeps it and hands it to moe_expert_bwd saves that
+ *                  call one [cap,f] store; with NULL it goes to ws and the backward recomputes it.
  *   o  [cap,d]     out.  Rows >= R of every output are left untouched.
  *   ws             device scratch (holds a [cap,f] and the tile-scheduler counters),
  *                  moe_workspace_bytes(MOE_WS_EXPERT_FWD, ...) bytes, 256-byte aligned
@@ -141,7 +144,7 @@ int moe_dispatch_static(const void* x, int dtype, int T, int d, int k, const int
  */
 int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
                    const int32_t* offsets, const void* w1, const void* w3, const void* w2,
-                   void* h1, void* h3, void* o, void* ws, size_t ws_bytes, moe_stream_t stream);
+                   void* h1, void* h3, void* a, void* o, void* ws, size_t ws_bytes, moe_stream_t stream);
 
 /*
  * moe_expert_bwd -- backward of moe_expert_fwd (AF-Pipe section: FFN workers run backward
@@ -153,6 +156,10 @@ int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
  * with silu'(z) = s(z) (1 + z (1 - s(z))), s the logistic function.
  *
  *   xp,h1,h3 as saved by the forward; d_o [cap,d] gradient w.r.t. o
+ *   a [cap,f]     the forward's activation output, or NULL.  With NULL it is recomputed from the saved
+ *                 (rounded) h1, h3 into ws, which differs from the forward's value by one rounding of
+ *                 h1 and h3; with the forward's copy dW2 is the gradient of exactly what the forward
+ *                 multiplied by W2, and the call stores one [cap,f] matrix less.
  *   dxp [cap,d] out; dw1,dw3 [e_cnt,d,f], dw2 [e_cnt,f,d] out (dtype = weight dtype)
  *   accumulate    0: dw* are overwritten (an expert without rows gets zeros);
  *                 1: the new gradient is added to the existing contents.
@@ -163,7 +170,7 @@ int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
  * Results are bit-reproducible from run to run (every sum has a fixed order).
  * Same shape restrictions as the forward.
  */
-int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d_o, int dtype,
+int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* a, const void* d_o, int dtype,
                    int cap, int d, int f, int e_cnt, const int32_t* offsets, const void* w1,
                    const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
                    int accumulate, void* ws, size_t ws_bytes, moe_stream_t stream);

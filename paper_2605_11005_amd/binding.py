@@ -51,9 +51,9 @@ def load_library():
                                         c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     lib.moe_expert_fwd.restype = c_int
     lib.moe_expert_fwd.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p,
-                                   c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.moe_expert_bwd.restype = c_int
-    lib.moe_expert_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p,
+    lib.moe_expert_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p,
                                    c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int,
                                    c_void_p, c_size_t, c_void_p]
     lib.moe_combine.restype = c_int
@@ -160,31 +160,31 @@ def moe_dispatch_static(x, k, topk_idx, row_scale, e_lo, e_cnt, offsets, perm, i
            "moe_dispatch_static")
 
 
-def moe_expert_fwd(xp, offsets, w1, w3, w2, h1, h3, o, ws):
+def moe_expert_fwd(xp, offsets, w1, w3, w2, h1, h3, o, ws, a=None):
     import torch
     cap, d = xp.shape
     e_cnt, _, f = w1.shape
     _need(xp, name="xp"); _need(o, xp.dtype, (cap, d), "o")
     _need(w1, xp.dtype, (e_cnt, d, f), "w1"); _need(w3, xp.dtype, (e_cnt, d, f), "w3")
     _need(w2, xp.dtype, (e_cnt, f, d), "w2")
-    _need(h1, xp.dtype, (cap, f), "h1"); _need(h3, xp.dtype, (cap, f), "h3")
+    _need(h1, xp.dtype, (cap, f), "h1"); _need(h3, xp.dtype, (cap, f), "h3"); _need(a, xp.dtype, (cap, f), "a")
     _need(offsets, torch.int32, (e_cnt + 1,), "offsets"); _need(ws, name="ws")
     _check(load_library().moe_expert_fwd(_ptr(xp), _dtype_code(xp), cap, d, f, e_cnt, _ptr(offsets), _ptr(w1), _ptr(w3),
-                                         _ptr(w2), _ptr(h1), _ptr(h3), _ptr(o), _ptr(ws),
+                                         _ptr(w2), _ptr(h1), _ptr(h3), _ptr(a), _ptr(o), _ptr(ws),
                                          ws.numel() * ws.element_size(), _stream()), "moe_expert_fwd")
 
 
-def moe_expert_bwd(xp, h1, h3, d_o, offsets, w1, w3, w2, dxp, dw1, dw3, dw2, accumulate, ws):
+def moe_expert_bwd(xp, h1, h3, d_o, offsets, w1, w3, w2, dxp, dw1, dw3, dw2, accumulate, ws, a=None):
     import torch
     cap, d = xp.shape
     e_cnt, _, f = w1.shape
     dt = xp.dtype
-    _need(xp, name="xp"); _need(h1, dt, (cap, f), "h1"); _need(h3, dt, (cap, f), "h3")
+    _need(xp, name="xp"); _need(h1, dt, (cap, f), "h1"); _need(h3, dt, (cap, f), "h3"); _need(a, dt, (cap, f), "a")
     _need(d_o, dt, (cap, d), "d_o"); _need(dxp, dt, (cap, d), "dxp")
     _need(w1, dt, (e_cnt, d, f), "w1"); _need(w3, dt, (e_cnt, d, f), "w3"); _need(w2, dt, (e_cnt, f, d), "w2")
     _need(dw1, dt, (e_cnt, d, f), "dw1"); _need(dw3, dt, (e_cnt, d, f), "dw3"); _need(dw2, dt, (e_cnt, f, d), "dw2")
     _need(offsets, torch.int32, (e_cnt + 1,), "offsets"); _need(ws, name="ws")
-    _check(load_library().moe_expert_bwd(_ptr(xp), _ptr(h1), _ptr(h3), _ptr(d_o), _dtype_code(xp), cap, d, f, e_cnt,
+    _check(load_library().moe_expert_bwd(_ptr(xp), _ptr(h1), _ptr(h3), _ptr(a), _ptr(d_o), _dtype_code(xp), cap, d, f, e_cnt,
                                          _ptr(offsets), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(dxp), _ptr(dw1), _ptr(dw3),
                                          _ptr(dw2), int(accumulate), _ptr(ws), ws.numel() * ws.element_size(),
                                          _stream()), "moe_expert_bwd")

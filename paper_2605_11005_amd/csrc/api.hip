@@ -269,29 +269,29 @@ int moe_dispatch_static(const void* x, int dtype, int T, int d, int k, const int
 
 int moe_expert_fwd(const void* xp, int dtype, int cap, int d, int f, int e_cnt,
                    const int32_t* offsets, const void* w1, const void* w3, const void* w2,
-                   void* h1, void* h3, void* o, void* ws, size_t ws_bytes, moe_stream_t stream) {
+                   void* h1, void* h3, void* a_out, void* o, void* ws, size_t ws_bytes, moe_stream_t stream) {
   int rc = shape_check_expert(dtype, cap, d, f, e_cnt);
   if (rc) return rc;
   if (!offsets) return MOE_EINVAL;
   if ((h1 == nullptr) != (h3 == nullptr)) return MOE_EINVAL;
   if (e_cnt > 0 && (!w1 || !w3 || !w2)) return MOE_EINVAL;
   if (cap > 0 && (!xp || !o)) return MOE_EINVAL;
-  if (misaligned(xp, 16) || misaligned(o, 16) || misaligned(h1, 16) || misaligned(h3, 16) ||
+  if (misaligned(xp, 16) || misaligned(o, 16) || misaligned(h1, 16) || misaligned(h3, 16) || misaligned(a_out, 16) ||
       misaligned(w1, 16) || misaligned(w3, 16) || misaligned(w2, 16))
     return MOE_EINVAL;
   if (!ws || misaligned(ws, 256) || ws_bytes < moe_workspace_bytes(MOE_WS_EXPERT_FWD, dtype, 0, 0, d, f, e_cnt, cap))
     return MOE_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   if (dtype == MOE_BF16)
-    return launch_expert_fwd_bf16(xp, cap, d, f, e_cnt, offsets, w1, w3, w2, h1, h3, o, ws, s);
-  float* a = (float*)ws;
-  float* t1 = h1 ? (float*)h1 : a + (size_t)cap * f;
-  float* t3 = h3 ? (float*)h3 : a + 2 * (size_t)cap * f;
+    return launch_expert_fwd_bf16(xp, cap, d, f, e_cnt, offsets, w1, w3, w2, h1, h3, a_out, o, ws, s);
+  float* a = a_out ? (float*)a_out : (float*)ws;
+  float* t1 = h1 ? (float*)h1 : (float*)ws + (size_t)cap * f;
+  float* t3 = h3 ? (float*)h3 : (float*)ws + 2 * (size_t)cap * f;
   return launch_expert_fwd_f32((const float*)xp, cap, d, f, e_cnt, offsets, (const float*)w1, (const float*)w3,
                                (const float*)w2, t1, t3, (float*)o, a, s);
 }
 
-int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d_o, int dtype,
+int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* a_in, const void* d_o, int dtype,
                    int cap, int d, int f, int e_cnt, const int32_t* offsets, const void* w1,
                    const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
                    int accumulate, void* ws, size_t ws_bytes, moe_stream_t stream) {
@@ -300,7 +300,7 @@ int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d
   if (!offsets || (accumulate != 0 && accumulate != 1)) return MOE_EINVAL;
   if (e_cnt > 0 && (!w1 || !w3 || !w2 || !dw1 || !dw3 || !dw2)) return MOE_EINVAL;
   if (cap > 0 && (!xp || !h1 || !h3 || !d_o || !dxp)) return MOE_EINVAL;
-  if (misaligned(xp, 16) || misaligned(h1, 16) || misaligned(h3, 16) || misaligned(d_o, 16) ||
+  if (misaligned(xp, 16) || misaligned(h1, 16) || misaligned(h3, 16) || misaligned(d_o, 16) || misaligned(a_in, 16) ||
       misaligned(dxp, 16) || misaligned(w1, 16) || misaligned(w3, 16) || misaligned(w2, 16) ||
       misaligned(dw1, 16) || misaligned(dw3, 16) || misaligned(dw2, 16))
     return MOE_EINVAL;
@@ -308,9 +308,9 @@ int moe_expert_bwd(const void* xp, const void* h1, const void* h3, const void* d
     return MOE_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   if (dtype == MOE_BF16)
-    return launch_expert_bwd_bf16(xp, h1, h3, d_o, cap, d, f, e_cnt, offsets, w1, w3, w2, dxp, dw1, dw3, dw2,
+    return launch_expert_bwd_bf16(xp, h1, h3, a_in, d_o, cap, d, f, e_cnt, offsets, w1, w3, w2, dxp, dw1, dw3, dw2,
                                   accumulate, ws, s);
-  return launch_expert_bwd_f32((const float*)xp, (const float*)h1, (const float*)h3, (const float*)d_o, cap, d, f,
+  return launch_expert_bwd_f32((const float*)xp, (const float*)h1, (const float*)h3, (const float*)a_in, (const float*)d_o, cap, d, f,
                                e_cnt, offsets, (const float*)w1, (const float*)w3, (const float*)w2, (float*)dxp,
                                (float*)dw1, (float*)dw3, (float*)dw2, accumulate, (float*)ws, s);
 }

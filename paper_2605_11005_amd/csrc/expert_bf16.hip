@@ -868,7 +868,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
                 w1[i] = pack_bf16x2(d1[2 * i], d1[2 * i + 1]);
                 w3[i] = pack_bf16x2(d3[2 * i], d3[2 * i + 1]);
               }
-              *reinterpret_cast<uint4*>(p.C0 + idx) = oa;
+              if (p.C0) *reinterpret_cast<uint4*>(p.C0 + idx) = oa;      // not stored when the forward's copy is at hand
               *reinterpret_cast<uint4*>(p.C1 + idx) = o1;
               *reinterpret_cast<uint4*>(p.C2 + idx) = o3;
             } else if (MODE == WG && PARTIAL) {   // one piece of a cut expert: fp32 partial tile
@@ -996,28 +996,29 @@ int launch_gg(const GArgs& a, hipStream_t s) {
 }  // namespace
 
 int launch_expert_fwd_bf16(const void* xp, int cap, int d, int f, int e_cnt, const int32_t* offsets,
-                           const void* w1, const void* w3, const void* w2, void* h1, void* h3, void* o,
+                           const void* w1, const void* w3, const void* w2, void* h1, void* h3, void* a_out, void* o,
                            void* a_ws, hipStream_t s) {
   if (cap == 0 || e_cnt == 0) return MOE_OK;
+  bf16_t* act = a_out ? (bf16_t*)a_out : (bf16_t*)a_ws;
   int32_t* sched = sched_area(a_ws, (size_t)cap * f * 2);
   hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, sched, 16);
   HIP_CHECK_LAUNCH();
   GArgs u = {};
   u.A0 = u.A1 = (const bf16_t*)xp; u.lda = d;
   u.B0 = (const bf16_t*)w1; u.B1 = (const bf16_t*)w3; u.ldb = f; u.b_es = (long)d * f;
-  u.C0 = (bf16_t*)h1; u.C1 = (bf16_t*)h3; u.C2 = (bf16_t*)a_ws; u.ldc = f;
+  u.C0 = (bf16_t*)h1; u.C1 = (bf16_t*)h3; u.C2 = act; u.ldc = f;
   u.off = offsets; u.sched = sched; u.e_cnt = e_cnt; u.N = f; u.K = d; u.save_h = (h1 && h3) ? 1 : 0;
   int rc = launch_gg<UP>(u, s);
   if (rc) return rc;
   GArgs w = {};
-  w.A0 = w.A1 = (const bf16_t*)a_ws; w.lda = f;
+  w.A0 = w.A1 = act; w.lda = f;
   w.B0 = w.B1 = (const bf16_t*)w2; w.ldb = d; w.b_es = (long)f * d;
   w.C0 = (bf16_t*)o; w.ldc = d;
   w.off = offsets; w.sched = sched + 8; w.e_cnt = e_cnt; w.N = d; w.K = f;
   return launch_gg<DOWN>(w, s);
 }
 
-int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const void* d_o, int cap,
+int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const void* a_in, const void* d_o, int cap,
                            int d, int f, int e_cnt, const int32_t* offsets, const void* w1,
                            const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
                            int accumulate, void* ws, hipStream_t s) {
@@ -1037,7 +1038,7 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
     GArgs g = {};   // dA = d_o W2^T, epilogue -> a, dH1, dH3
     g.A0 = g.A1 = (const bf16_t*)d_o; g.lda = d;
     g.B0 = g.B1 = (const bf16_t*)w2; g.ldb = d; g.b_es = (long)f * d;
-    g.C0 = a; g.C1 = dh1; g.C2 = dh3; g.ldc = f;
+    g.C0 = a_in ? nullptr : a; g.C1 = dh1; g.C2 = dh3; g.ldc = f;
     g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3;
     g.off = offsets; g.sched = sched; g.e_cnt = e_cnt; g.N = f; g.K = d;
     if ((rc = launch_gg<DA>(g, s))) return rc;
@@ -1049,7 +1050,7 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
     if ((rc = launch_gg<DX>(x, s))) return rc;
   }
   GArgs w = {};     // dW2 = a^T d_o
-  w.A0 = w.A1 = a; w.lda = f;
+  w.A0 = w.A1 = a_in ? (const bf16_t*)a_in : a; w.lda = f;
   w.B0 = w.B1 = (const bf16_t*)d_o; w.ldb = d;
   w.C0 = (bf16_t*)dw2; w.ldc = d; w.c_es = (long)f * d;
   w.off = offsets; w.sched = sched + 16; w.e_cnt = e_cnt; w.M = f; w.N = d; w.accumulate = accumulate;

@@ -170,7 +170,7 @@ int launch_expert_fwd_f32(const float* xp, int cap, int d, int f, int e_cnt, con
   return MOE_OK;
 }
 
-int launch_expert_bwd_f32(const float* xp, const float* h1, const float* h3, const float* d_o, int cap,
+int launch_expert_bwd_f32(const float* xp, const float* h1, const float* h3, const float* a_in, const float* d_o, int cap,
                           int d, int f, int e_cnt, const int32_t* offsets, const float* w1,
                           const float* w3, const float* w2, float* dxp, float* dw1, float* dw3,
                           float* dw2, int accumulate, float* ws, hipStream_t s) {
@@ -193,7 +193,8 @@ int launch_expert_bwd_f32(const float* xp, const float* h1, const float* h3, con
     HIP_CHECK_LAUNCH();
   }
   const int beta = accumulate ? 1 : 0;
-  hipLaunchKernelGGL(gemm_wgrad_f32, dim3((d + TN - 1) / TN, (f + TM - 1) / TM, e_cnt), blk, 0, s, a, f, d_o, d, dw2, f, d, offsets, beta);
+  // dW2 takes the activation the forward kept, if the caller passed it, else the one recomputed above
+  hipLaunchKernelGGL(gemm_wgrad_f32, dim3((d + TN - 1) / TN, (f + TM - 1) / TM, e_cnt), blk, 0, s, a_in ? a_in : a, f, d_o, d, dw2, f, d, offsets, beta);
   HIP_CHECK_LAUNCH();
   hipLaunchKernelGGL(gemm_wgrad_f32, dim3((f + TN - 1) / TN, (d + TM - 1) / TM, e_cnt), blk, 0, s, xp, d, dh1, f, dw1, d, f, offsets, beta);
   HIP_CHECK_LAUNCH();

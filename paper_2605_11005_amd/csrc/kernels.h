@@ -24,15 +24,15 @@ int launch_combine_rows(const void* o, int dtype, int T, int d, int k, const int
 int launch_expert_fwd_f32(const float* xp, int cap, int d, int f, int e_cnt, const int32_t* offsets,
                           const float* w1, const float* w3, const float* w2, float* h1, float* h3,
                           float* o, float* a_ws, hipStream_t s);
-int launch_expert_bwd_f32(const float* xp, const float* h1, const float* h3, const float* d_o, int cap,
+int launch_expert_bwd_f32(const float* xp, const float* h1, const float* h3, const float* a_in, const float* d_o, int cap,
                           int d, int f, int e_cnt, const int32_t* offsets, const float* w1,
                           const float* w3, const float* w2, float* dxp, float* dw1, float* dw3,
                           float* dw2, int accumulate, float* ws, hipStream_t s);
 
 int launch_expert_fwd_bf16(const void* xp, int cap, int d, int f, int e_cnt, const int32_t* offsets,
-                           const void* w1, const void* w3, const void* w2, void* h1, void* h3, void* o,
+                           const void* w1, const void* w3, const void* w2, void* h1, void* h3, void* a_out, void* o,
                            void* a_ws, hipStream_t s);
-int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const void* d_o, int cap,
+int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const void* a_in, const void* d_o, int cap,
                            int d, int f, int e_cnt, const int32_t* offsets, const void* w1,
                            const void* w3, const void* w2, void* dxp, void* dw1, void* dw3, void* dw2,
                            int accumulate, void* ws, hipStream_t s);

@@ -58,7 +58,9 @@ class MoeLayerBuffers:
         nb = lambda which: B.moe_workspace_bytes(which, code, T, k, d, f, ec, cap)
         self.ws_dispatch = torch.empty(nb(B.WS_DISPATCH), dtype=torch.uint8, device=device)
         self.ws_fwd = torch.empty(nb(B.WS_EXPERT_FWD), dtype=torch.uint8, device=device)
+        self.a = None
         if grads:
+            self.a = torch.empty((cap, f), dtype=dt, device=device)      # kept by the forward for the backward
             self.d_o = torch.empty((cap, d), dtype=dt, device=device)
             self.dxp = torch.empty((cap, d), dtype=dt, device=device)
             self.dx = torch.empty((T, d), dtype=dt, device=device)
@@ -85,7 +87,7 @@ def run_forward(wl, dev, buf: MoeLayerBuffers):
     B.moe_route(dev["logits"], wl.k, wl.gate_mode, wl.e_lo, wl.e_cnt, buf.topk_idx, buf.topk_w, buf.counts)
     B.moe_dispatch(dev["x"], wl.k, buf.topk_idx, None, wl.e_lo, wl.e_cnt, buf.offsets, buf.perm, buf.inv, False,
                    buf.xp, buf.ws_dispatch)
-    B.moe_expert_fwd(buf.xp, buf.offsets, dev["w1"], dev["w3"], dev["w2"], buf.h1, buf.h3, buf.o, buf.ws_fwd)
+    B.moe_expert_fwd(buf.xp, buf.offsets, dev["w1"], dev["w3"], dev["w2"], buf.h1, buf.h3, buf.o, buf.ws_fwd, a=buf.a)
     B.moe_combine(buf.o, buf.inv, buf.topk_w, buf.y)
 
 
@@ -93,7 +95,7 @@ def run_backward(wl, dev, buf: MoeLayerBuffers, accumulate: bool = False):
     B.moe_dispatch(dev["dy"], wl.k, None, buf.topk_w, wl.e_lo, wl.e_cnt, buf.offsets, buf.perm, buf.inv, True,
                    buf.d_o, None)
     B.moe_expert_bwd(buf.xp, buf.h1, buf.h3, buf.d_o, buf.offsets, dev["w1"], dev["w3"], dev["w2"], buf.dxp,
-                     buf.dw1, buf.dw3, buf.dw2, accumulate, buf.ws_bwd)
+                     buf.dw1, buf.dw3, buf.dw2, accumulate, buf.ws_bwd, a=buf.a)
     B.moe_combine(buf.dxp, buf.inv, None, buf.dx)
 
 
@@ -103,7 +105,7 @@ def run_forward_router(wl, dev, buf: MoeLayerBuffers):
     B.moe_route(buf.logits, wl.k, wl.gate_mode, wl.e_lo, wl.e_cnt, buf.topk_idx, buf.topk_w, buf.counts)
     B.moe_dispatch(dev["x"], wl.k, buf.topk_idx, None, wl.e_lo, wl.e_cnt, buf.offsets, buf.perm, buf.inv, False,
                    buf.xp, buf.ws_dispatch)
-    B.moe_expert_fwd(buf.xp, buf.offsets, dev["w1"], dev["w3"], dev["w2"], buf.h1, buf.h3, buf.o, buf.ws_fwd)
+    B.moe_expert_fwd(buf.xp, buf.offsets, dev["w1"], dev["w3"], dev["w2"], buf.h1, buf.h3, buf.o, buf.ws_fwd, a=buf.a)
     B.moe_combine(buf.o, buf.inv, buf.topk_w, buf.y)
 
 
@@ -111,7 +113,7 @@ def run_backward_router(wl, dev, buf: MoeLayerBuffers, accumulate: bool = False)
     """Backward including the gate: dx = expert-path term + router term; dwr = gradient of Wr."""
     B.moe_combine_bwd(dev["dy"], buf.o, buf.inv, buf.topk_w, buf.d_o, buf.dgate)
     B.moe_expert_bwd(buf.xp, buf.h1, buf.h3, buf.d_o, buf.offsets, dev["w1"], dev["w3"], dev["w2"], buf.dxp,
-                     buf.dw1, buf.dw3, buf.dw2, accumulate, buf.ws_bwd)
+                     buf.dw1, buf.dw3, buf.dw2, accumulate, buf.ws_bwd, a=buf.a)
     B.moe_combine(buf.dxp, buf.inv, None, buf.dx)
     B.moe_gate_bwd(buf.logits, buf.topk_idx, buf.dgate, wl.gate_mode, buf.dlogits)
     B.moe_router_bwd(dev["x"], dev["wr"], buf.dlogits, buf.dwr, accumulate, buf.dx, True, buf.ws_router)

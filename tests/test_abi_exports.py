@@ -67,10 +67,10 @@ def test_host_validation_rejects_before_launch(lib):
     assert lib.moe_dispatch(fake, 1, 4, 16, 2, fake, None, 0, 4, fake, fake, fake, 0, fake, 8, None, 0, None) == 3
     assert lib.moe_dispatch(fake, 5, 4, 16, 2, fake, None, 0, 4, fake, fake, fake, 0, fake, 8, fake, 1 << 20, None) == 1
     # experts: bf16 needs d, f multiples of 64; workspace size is checked
-    assert lib.moe_expert_fwd(fake, 1, 8, 96, 64, 2, fake, fake, fake, fake, None, None, fake, fake, 1 << 20, None) == 2
-    assert lib.moe_expert_fwd(fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, None, None, fake, fake, 16, None) == 3
-    assert lib.moe_expert_fwd(fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, None, fake, fake, 1 << 20, None) == 1
-    assert lib.moe_expert_bwd(fake, fake, fake, fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, fake, fake, fake,
+    assert lib.moe_expert_fwd(fake, 1, 8, 96, 64, 2, fake, fake, fake, fake, None, None, None, fake, fake, 1 << 20, None) == 2
+    assert lib.moe_expert_fwd(fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, None, None, None, fake, fake, 16, None) == 3
+    assert lib.moe_expert_fwd(fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, None, None, fake, fake, 1 << 20, None) == 1
+    assert lib.moe_expert_bwd(fake, fake, fake, None, fake, 1, 8, 64, 64, 2, fake, fake, fake, fake, fake, fake, fake, fake,
                               2, fake, 1 << 20, None) == 1
     # a NULL tensor with T > 0 is rejected on the host (it would be dereferenced on the device)
     assert lib.moe_combine(None, 1, 4, 16, 2, fake, None, fake, None) == 1
@@ -80,7 +80,7 @@ def test_host_validation_rejects_before_launch(lib):
     assert lib.moe_combine_bwd(fake, fake, 1, 4, 16, 2, fake, fake, None, fake, None) == 1
     assert lib.moe_combine_bwd(None, fake, 1, 4, 16, 2, fake, fake, fake, fake, None) == 1
     # fp32 experts: row tiles beyond the grid's second dimension are refused by validation, not by the launch
-    assert lib.moe_expert_fwd(fake, 0, 64 * 65536, 64, 64, 2, fake, fake, fake, fake, None, None, fake, fake, 1 << 40, None) == 2
+    assert lib.moe_expert_fwd(fake, 0, 64 * 65536, 64, 64, 2, fake, fake, fake, fake, None, None, None, fake, fake, 1 << 40, None) == 2
     assert lib.moe_combine(fake, 1, 4, 12, 2, fake, None, fake, None) == 2
     # the entry point without a workspace argument refuses plans larger than its built-in scratch:
     # 2^22 tokens x top-8 over 1024 local experts need a 268 MB chunk table

@@ -154,6 +154,28 @@ def test_forward_only_without_saved_activations(wl):
     assert (o2[R:] == 9.0).all(), "rows past R are left untouched"
 
 
+@pytest.mark.parametrize("wl", [W.TINY, W.DSV3.scaled(name="dsv3-recompute-a", T=3000, d=256, f=320)], ids=lambda w: w.name)
+def test_backward_without_the_kept_activation(wl):
+    """a = NULL in both calls: the forward keeps only h1, h3 and the backward recomputes the activation.
+    Every gradient still matches the oracle; dxp, dW1, dW3 do not depend on the kept copy at all."""
+    from paper_2605_11005_amd.layer import run_backward
+    inp = make_inputs(wl)
+    fw, bw = oracle_layer(wl, inp)
+    dev, buf = gpu_layer(wl, inp)
+    kept = {n: getattr(buf, n).clone() for n in ("dxp", "dw1", "dw3", "dw2")}
+    for n in kept:
+        getattr(buf, n).fill_(float("nan"))
+    buf.a = None
+    run_backward(wl, dev, buf)
+    torch.cuda.synchronize()
+    check_layer(wl, inp, fw, bw, buf)
+    R = int(fw["offsets"][-1])
+    assert torch.equal(buf.dxp[:R], kept["dxp"][:R]), "dxp"
+    for n in ("dw1", "dw3"):
+        assert torch.equal(getattr(buf, n), kept[n]), n
+    assert rel_err(host(buf.dw2), host(kept["dw2"])) < TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("T", [1, 5, 63])
 def test_bf16_tiny_batches(T):
     wl = W.DSV3.scaled(name=f"dsv3-T{T}", T=T, d=128, f=64, E=16, e_lo=4, e_cnt=8, k=4)
