@@ -42,6 +42,10 @@ def main():
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the compact records of the other configurations (default run of the headline workload only)")
     ap.add_argument("--other-steps", type=int, default=5, help="timed steps per workload of the other_workloads block")
+    ap.add_argument("--drop-experts-below", type=int, default=0,
+                    help="diagnostic: local experts that would receive fewer rows than this are masked out of the routing "
+                         "(their logits are set to -1e30, so their tokens go elsewhere and they get no rows); shows what the "
+                         "experts with a handful of rows cost.  Not the headline workload: the line says so in config")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the MFMA-only / copy / vendor-GEMM ceiling kernels (counter runs that only need the step)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -92,6 +96,16 @@ def run_workload(wl, steps, warmup, full, args):
     t0 = time.time()
     x = W.tokens(wl)
     logits = W.router_logits(wl, x)
+    dropped = []
+    if full and args.drop_experts_below > 0:
+        lt = torch.from_numpy(logits).cuda()
+        c0 = torch.empty((wl.e_cnt,), dtype=torch.int32, device="cuda")
+        B.moe_route(lt, wl.k, wl.gate_mode, wl.e_lo, wl.e_cnt, torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda"),
+                    torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda"), c0)
+        dropped = [wl.e_lo + e for e, c in enumerate(c0.cpu().tolist()) if c < args.drop_experts_below]
+        logits = logits.copy()
+        logits[:, dropped] = -1e30
+        del lt, c0
     dy = W.out_grad(wl)
     w1, w3, w2 = W.all_expert_weights(wl, out_bits=bf16)
     dt = torch_dtype(wl)
@@ -192,6 +206,9 @@ def run_workload(wl, steps, warmup, full, args):
     config = {"workload": wl.name, "T": T, "d": d, "E": wl.E, "local_experts": wl.e_cnt, "k": k, "f": f,
               "gate_mode": wl.gate_mode, "routed_rows_R": R, "tokens_with_local_slot_U": U,
               "rows_per_expert_min_max": [int(counts.min()), int(counts.max())]}
+    if dropped:
+        config["workload"] = wl.name + f" with {len(dropped)} local experts below {args.drop_experts_below} rows masked out of the routing"
+        config["experts_masked_out"] = dropped
     if not full:
         rec = {"value": value, "unit": "TFLOP/s", "ms_per_step": ms_per_step, "steps": steps, "dtype": wl.dtype,
                "config": config,
@@ -317,10 +334,22 @@ def measured_ceilings(B, torch):
         flop = B.moe_probe_mfma_bf16(sink, 4000, rnd)
         t = timed(lambda: B.moe_probe_mfma_bf16(sink, 4000, rnd), 20)    # ~20 ms of sustained load
         out[tag] = flop / t / 1e12
+    # the same loop with random operands re-read from LDS at the grouped GEMM's rate: what the matrix cores
+    # sustain under the package power limit once their operand feed is paid for
+    for tag, feed in (("mfma_bf16_random_operands_lds_16B_reads_TFLOPs", 1), ("mfma_bf16_random_operands_lds_transposing_reads_TFLOPs", 2)):
+        flop = B.moe_probe_mfma_fed_bf16(sink, 4000, feed)
+        t = timed(lambda: B.moe_probe_mfma_fed_bf16(sink, 4000, feed), 20)
+        out[tag] = flop / t / 1e12
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-    dst = torch.empty_like(src)
+    dst = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
     t = timed(lambda: B.moe_probe_copy(src, dst), 10)
     out["device_copy_GBps"] = 2.0 * (1 << 30) / t / 1e9
+    # streaming kernels with the row movers' access width over 1 GiB: fill, read, one read fanned out to two
+    # writes (the dispatch's mix at the headline share: 2.2 rows written per row read)
+    word = torch.zeros(16, dtype=torch.int32, device="cuda")
+    for tag, writes, moved in (("stream_fill_GBps", 0, 1.0), ("stream_read_GBps", -1, 1.0), ("stream_1_read_2_writes_GBps", 2, 3.0)):
+        t = timed(lambda: B.moe_probe_stream(src, dst, writes, word), 10)
+        out[tag] = moved * (1 << 30) / t / 1e9
     del src, dst
     # yardstick only: the vendor library's dense bf16 GEMM (torch.matmul) on one large problem of
     # the up-projection's shape and operand layout, random operands

@@ -283,11 +283,22 @@ int moe_profile_stats(int kernel, double* min_ms /* host */, double* median_ms /
  *                        is the realistic case: switching activity lowers the sustained clock).
  *                        sink: device scratch of >= 256*4 bytes per CU; *flop (host) receives
  *                        the FLOP count of the launch.
+ *   moe_probe_mfma_fed_bf16  the same loop with random operands re-read from LDS before every 16 MFMAs, at
+ *                        the rate the grouped GEMM's tiling needs (8 fragments of 16 bytes per lane):
+ *                        feed = 1 with 16-byte reads, feed = 2 with pairs of 8-byte transposing reads.  It
+ *                        prices the operand feed under the package power limit.
  *   moe_probe_copy       enqueues a plain device copy of `bytes` (multiple of 16) bytes.
+ *   moe_probe_stream     streaming kernels with the row movers' access width, for their ceilings: over
+ *                        `bytes` (multiple of 16) of src, writes = -1 reads only (sink: >= 4 bytes of device
+ *                        memory, never written in practice), 0 fills dst, n = 1..3 reads each 16-byte vector
+ *                        once and writes it n times (dst must hold n * bytes).
  */
 int moe_probe_mfma_bf16(float* sink, size_t sink_bytes, int iters, int random_operands, double* flop /* host */,
                         moe_stream_t stream);
+int moe_probe_mfma_fed_bf16(float* sink, size_t sink_bytes, int iters, int feed, double* flop /* host */,
+                            moe_stream_t stream);
 int moe_probe_copy(const void* src, void* dst, size_t bytes, moe_stream_t stream);
+int moe_probe_stream(const void* src, void* dst, size_t bytes, int writes, void* sink, moe_stream_t stream);
 
 /* Static, human-readable text for an error code. */
 const char* moe_error_string(int code);

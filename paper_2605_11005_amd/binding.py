@@ -19,7 +19,8 @@ _LIB = None
 
 EXPORTS = ("moe_route", "moe_dispatch", "moe_dispatch_static", "moe_expert_fwd", "moe_expert_bwd", "moe_combine",
            "moe_router_fwd", "moe_combine_bwd", "moe_gate_bwd", "moe_router_bwd",
-           "moe_profile_enable", "moe_profile_read", "moe_profile_stats", "moe_probe_mfma_bf16", "moe_probe_copy",
+           "moe_profile_enable", "moe_profile_read", "moe_profile_stats", "moe_probe_mfma_bf16", "moe_probe_mfma_fed_bf16",
+           "moe_probe_copy", "moe_probe_stream",
            "moe_workspace_bytes", "moe_error_string")
 
 
@@ -292,3 +293,28 @@ def moe_probe_copy(src, dst):
     lib.moe_probe_copy.restype = ctypes.c_int
     lib.moe_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     _check(lib.moe_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()), "moe_probe_copy")
+
+
+def moe_probe_mfma_fed_bf16(sink, iters: int, feed: int) -> float:
+    """Enqueue the MFMA loop whose operands are re-read from LDS (feed 1: 16-byte reads, 2: transposing
+    reads); returns the FLOP count of the launch."""
+    lib = load_library()
+    lib.moe_probe_mfma_fed_bf16.restype = ctypes.c_int
+    lib.moe_probe_mfma_fed_bf16.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                            ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    flop = ctypes.c_double(0)
+    _check(lib.moe_probe_mfma_fed_bf16(_ptr(sink), sink.numel() * sink.element_size(), int(iters), int(feed),
+                                       ctypes.byref(flop), _stream()), "moe_probe_mfma_fed_bf16")
+    return flop.value
+
+
+def moe_probe_stream(src, dst, writes: int, sink=None):
+    """Streaming ceiling kernels over src's bytes: writes = -1 read only, 0 fill dst, n >= 1 one read and n writes."""
+    lib = load_library()
+    lib.moe_probe_stream.restype = ctypes.c_int
+    lib.moe_probe_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p,
+                                     ctypes.c_void_p]
+    nbytes = src.numel() * src.element_size()
+    if writes >= 1 and dst.numel() * dst.element_size() < writes * nbytes:
+        raise MoeError("dst must hold `writes` copies of src")
+    _check(lib.moe_probe_stream(_ptr(src), _ptr(dst), nbytes, int(writes), _ptr(sink), _stream()), "moe_probe_stream")

@@ -122,6 +122,24 @@ int moe_probe_mfma_bf16(float* sink, size_t sink_bytes, int iters, int random_op
   return rc;
 }
 
+int moe_probe_mfma_fed_bf16(float* sink, size_t sink_bytes, int iters, int feed, double* flop, moe_stream_t stream) {
+  if (!sink || iters <= 0 || iters > (1 << 22) || (feed != 1 && feed != 2)) return MOE_EINVAL;
+  const int cus = device_cu_count();
+  if (sink_bytes < (size_t)cus * 256 * sizeof(float)) return MOE_EWORKSPACE;
+  int rc = launch_probe_mfma_fed(sink, iters, feed, (hipStream_t)stream);
+  if (rc == MOE_OK && flop) *flop = (double)cus * 4.0 * (double)iters * 16.0 * 32768.0;
+  return rc;
+}
+
+int moe_probe_stream(const void* src, void* dst, size_t bytes, int writes, void* sink, moe_stream_t stream) {
+  if (writes < -1 || writes > 3 || (bytes & 15)) return MOE_EINVAL;
+  if ((writes != 0 && (!src || misaligned(src, 16))) || (writes >= 0 && (!dst || misaligned(dst, 16))) ||
+      (writes < 0 && (!sink || misaligned(sink, 4))))
+    return MOE_EINVAL;
+  if (bytes / 16 / 256 >= (1ull << 31)) return MOE_EUNSUPPORTED;
+  return launch_probe_stream(src, dst, bytes, writes, (uint32_t*)sink, (hipStream_t)stream);
+}
+
 int moe_probe_copy(const void* src, void* dst, size_t bytes, moe_stream_t stream) {
   if (!src || !dst || (bytes & 15) || misaligned(src, 16) || misaligned(dst, 16)) return MOE_EINVAL;
   if (bytes / 16 / 256 >= (1ull << 31)) return MOE_EUNSUPPORTED;

@@ -62,6 +62,8 @@ size_t wgrad_split_bytes(int d, int f);
 
 int launch_probe_mfma(float* sink, int iters, int random_operands, hipStream_t s);
 int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+int launch_probe_mfma_fed(float* sink, int iters, int feed, hipStream_t s);
+int launch_probe_stream(const void* src, void* dst, size_t bytes, int writes, uint32_t* sink, hipStream_t s);
 
 int device_cu_count();
 
