@@ -46,6 +46,9 @@ def main():
                     help="diagnostic: local experts that would receive fewer rows than this are masked out of the routing "
                          "(their logits are set to -1e30, so their tokens go elsewhere and they get no rows); shows what the "
                          "experts with a handful of rows cost.  Not the headline workload: the line says so in config")
+    ap.add_argument("--power-seconds", type=float, default=0.0,
+                    help="after the timed region keep running steps for this many seconds while a child process reads the "
+                         "package power and shader clock (rocm-smi) once a second; the samples go into `power_and_clock`")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the MFMA-only / copy / vendor-GEMM ceiling kernels (counter runs that only need the step)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -222,6 +225,7 @@ def run_workload(wl, steps, warmup, full, args):
         torch.cuda.empty_cache()
         return rec, None
 
+    power = power_and_clock(torch, step, args.power_seconds) if args.power_seconds > 0 else None
     # enabling the profiler again starts a new log: the step's figures were read above
     router = None if args.no_router else router_row(B, C, W, torch, wl, dev, buf, R, U, b)
     chunked = {str(c): chunked_ms(torch, wl, dev, c, warmup, steps) for c in args.chunks}
@@ -245,6 +249,8 @@ def run_workload(wl, steps, warmup, full, args):
         "dispatch_combine_GBps": [hbm.get("dispatch", {}).get("achieved"), hbm.get("combine", {}).get("achieved")],
         "input_generation_s": gen_s,
     }
+    if power:
+        out["power_and_clock"] = power
     if router:
         out["trainable_gate"] = router
     if chunked:
@@ -252,6 +258,83 @@ def run_workload(wl, steps, warmup, full, args):
     del dev, buf
     torch.cuda.empty_cache()
     return out, (x, logits, dy)
+
+
+def power_and_clock(torch, step, seconds):
+    """Package power and shader clock while the steps run back to back: a sampler thread starts `rocm-smi` as a
+    child process about once a second (a read-only query) while this thread keeps the GPU busy."""
+    import re
+    import subprocess
+    import threading
+    samples, stop = [], threading.Event()
+
+    def find(obj, name):
+        """First value stored under a key called `name` anywhere in a nested JSON object."""
+        if isinstance(obj, dict):
+            for key, val in obj.items():
+                if key.lower() == name:
+                    return val
+                got = find(val, name)
+                if got is not None:
+                    return got
+        elif isinstance(obj, list):
+            for val in obj:
+                got = find(val, name)
+                if got is not None:
+                    return got
+        return None
+
+    def number(val):
+        if isinstance(val, dict):
+            val = val.get("value")
+        m = re.search(r"([0-9]+(?:\.[0-9]+)?)", str(val))
+        return float(m.group(1)) if m else None
+
+    def sampler():
+        time.sleep(min(3.0, seconds / 4))            # let the clocks settle under load first
+        while not stop.is_set():
+            rec = {}
+            try:                                     # shader clock and the power limit
+                txt = subprocess.run(["rocm-smi", "--showclocks", "--showmaxpower", "--json"], capture_output=True, text=True,
+                                     timeout=10).stdout
+                for key, val in next(iter(json.loads(txt).values())).items():
+                    lk = key.lower()
+                    if "max" in lk and "power" in lk:
+                        rec["power_cap_W"] = number(val)
+                    elif lk.startswith("sclk") and "level" not in lk:
+                        rec["sclk_MHz"] = number(val)
+            except Exception as exc:                 # the queries are a courtesy: report, never fail the benchmark
+                rec["rocm_smi_error"] = str(exc)[:200]
+            try:                                     # package (socket) power
+                txt = subprocess.run(["amd-smi", "metric", "-g", "0", "--power", "--json"], capture_output=True, text=True,
+                                     timeout=10).stdout
+                val = find(json.loads(txt), "socket_power")
+                if val is not None:
+                    rec["package_power_W"] = number(val)
+            except Exception as exc:
+                rec["amd_smi_error"] = str(exc)[:200]
+            samples.append(rec)
+            stop.wait(1.0)
+
+    th = threading.Thread(target=sampler, daemon=True)
+    th.start()
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+        n += 5
+    busy = time.perf_counter() - t0
+    stop.set()
+    th.join(timeout=15)
+    def med(key):
+        vals = sorted(r[key] for r in samples if r.get(key) is not None)
+        return vals[len(vals) // 2] if vals else None
+
+    return {"seconds": busy, "steps": n, "ms_per_step": busy * 1e3 / n if n else None, "samples": samples,
+            "median_package_power_W": med("package_power_W"), "median_sclk_MHz": med("sclk_MHz"),
+            "power_cap_W": med("power_cap_W")}
 
 
 def router_row(B, C, W, torch, wl, dev, buf, R, U, b, reps=10):
