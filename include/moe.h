@@ -248,8 +248,9 @@ int moe_router_bwd(const void* x, const void* wr, const float* dlogits, int dtyp
 
 /*
  * Optional per-kernel timing, for benchmarks (measurement of the grouped GEMMs against the
- * MFMA roofline and of the row movers against HBM bandwidth).  This is the library's only
- * process-wide state and is off by default.  While enabled, every kernel launch of the
+ * MFMA roofline and of the row movers against HBM bandwidth).  Apart from per-device caches of
+ * constants (CU count, the kernels' LDS opt-in attribute, the address of the built-in plan scratch)
+ * this is the library's only process-wide state, and it is off by default.  While enabled, every kernel launch of the
  * entry points above is bracketed by a pair of hipEvents recorded on the call's stream
  * (a few microseconds of host work per launch; no synchronisation).
  *   moe_profile_enable(on)   on != 0: create the event pool (first time) and start recording
