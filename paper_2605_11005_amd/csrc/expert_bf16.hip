@@ -36,6 +36,14 @@
 
 namespace {
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// 16-byte store of a finished output vector.  The epilogues' bf16 outputs stream out once (2-8 GB per step) and
+// are next read by another kernel: a nontemporal store keeps them from displacing operand panels in the caches
+// (measured: -0.3 % at the DeepSeek-V3-like share, -0.5 % at the Mixtral-like layer over the six GEMMs).
+__device__ __forceinline__ void store16(void* ptr, uint4 v) {
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, v), reinterpret_cast<u32x4_t*>(ptr));
+}
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -753,10 +761,10 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               wa[i] = pack_bf16x2(silu_f(x1[2 * i]) * x3[2 * i], silu_f(x1[2 * i + 1]) * x3[2 * i + 1]);
             }
             if (p.save_h) {
-              *reinterpret_cast<uint4*>(p.C0 + idx) = o1;
-              *reinterpret_cast<uint4*>(p.C1 + idx) = o3;
+              store16(p.C0 + idx, o1);
+              store16(p.C1 + idx, o3);
             }
-            *reinterpret_cast<uint4*>(p.C2 + idx) = oa;
+            store16(p.C2 + idx, oa);
           } else if (PARTIAL) {   // WGD, one piece of a cut expert: fp32 partial tiles
             float* c0 = p.P0 + (size_t)ep_piece * p.p_stride + (size_t)grow * p.ldc + gcol;
             float* c1 = c0 + (size_t)p.M * p.N;
@@ -786,8 +794,8 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               w1[i] = pack_bf16x2(x1[2 * i], x1[2 * i + 1]);
               w3[i] = pack_bf16x2(x3[2 * i], x3[2 * i + 1]);
             }
-            *reinterpret_cast<uint4*>(c0) = o1;
-            *reinterpret_cast<uint4*>(c1) = o3;
+            store16(c0, o1);
+            store16(c1, o3);
           }
         }
       }
@@ -868,9 +876,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
                 w1[i] = pack_bf16x2(d1[2 * i], d1[2 * i + 1]);
                 w3[i] = pack_bf16x2(d3[2 * i], d3[2 * i + 1]);
               }
-              if (p.C0) *reinterpret_cast<uint4*>(p.C0 + idx) = oa;      // not stored when the forward's copy is at hand
-              *reinterpret_cast<uint4*>(p.C1 + idx) = o1;
-              *reinterpret_cast<uint4*>(p.C2 + idx) = o3;
+              if (p.C0) store16(p.C0 + idx, oa);      // not stored when the forward's copy is at hand
+              store16(p.C1 + idx, o1);
+              store16(p.C2 + idx, o3);
             } else if (MODE == WG && PARTIAL) {   // one piece of a cut expert: fp32 partial tile
               float* c0 = p.P0 + (size_t)ep_piece * p.p_stride + (size_t)grow * p.ldc + gcol;
               *reinterpret_cast<float4*>(c0) = make_float4(x[0], x[1], x[2], x[3]);
@@ -892,7 +900,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               uint32_t* w = reinterpret_cast<uint32_t*>(&o);
 #pragma unroll
               for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(x[2 * i], x[2 * i + 1]);
-              *reinterpret_cast<uint4*>(c0) = o;
+              store16(c0, o);
             }
           }
         }
