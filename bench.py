@@ -46,6 +46,10 @@ def main():
                     help="diagnostic: local experts that would receive fewer rows than this are masked out of the routing "
                          "(their logits are set to -1e30, so their tokens go elsewhere and they get no rows); shows what the "
                          "experts with a handful of rows cost.  Not the headline workload: the line says so in config")
+    ap.add_argument("--operand-data", choices=["workload", "constant", "zero"], default="workload",
+                    help="diagnostic: overwrite tokens, output gradient and expert weights with one constant (or zero) after "
+                         "routing; same kernels, same cycles, less switching activity in the matrix cores -- shows how far the "
+                         "package power limit, not the instruction stream, sets the rate.  Not the headline workload")
     ap.add_argument("--power-seconds", type=float, default=0.0,
                     help="after the timed region keep running steps for this many seconds while a child process reads the "
                          "package power and shader clock (rocm-smi) once a second; the samples go into `power_and_clock`")
@@ -115,6 +119,9 @@ def run_workload(wl, steps, warmup, full, args):
     dev = dict(x=to_device(x, dt), logits=to_device(logits, torch.float32), dy=to_device(dy, dt),
                w1=to_device(w1, dt, bf16), w3=to_device(w3, dt, bf16), w2=to_device(w2, dt, bf16))
     del w1, w3, w2
+    if full and args.operand_data != "workload":
+        for name, val in (("x", 1.0), ("dy", 1.0), ("w1", 0.5), ("w3", 0.5), ("w2", 0.5)):
+            dev[name].fill_(val if args.operand_data == "constant" else 0.0)
     gen_s = time.time() - t0
 
     # realised row count (outside the timed region) sizes the expert-order buffers
@@ -209,6 +216,8 @@ def run_workload(wl, steps, warmup, full, args):
     config = {"workload": wl.name, "T": T, "d": d, "E": wl.E, "local_experts": wl.e_cnt, "k": k, "f": f,
               "gate_mode": wl.gate_mode, "routed_rows_R": R, "tokens_with_local_slot_U": U,
               "rows_per_expert_min_max": [int(counts.min()), int(counts.max())]}
+    if full and args.operand_data != "workload":
+        config["workload"] = wl.name + f" with {args.operand_data} operand data (diagnostic)"
     if dropped:
         config["workload"] = wl.name + f" with {len(dropped)} local experts below {args.drop_experts_below} rows masked out of the routing"
         config["experts_masked_out"] = dropped
