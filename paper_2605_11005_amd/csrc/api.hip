@@ -177,7 +177,8 @@ int shape_check_router(int dtype, int T, int d, int E) {
   if (bad_dtype(dtype) || T < 0 || d <= 0 || E <= 0) return MOE_EINVAL;
   if (E > MOE_MAX_EXPERTS) return MOE_EUNSUPPORTED;
   if (dtype == MOE_BF16 && d % 8) return MOE_EUNSUPPORTED;
-  if ((long long)T * (d > E ? d : E) >= (1ll << 40) || T > (1 << 22)) return MOE_EUNSUPPORTED;
+  // (row tiles of 64 tokens sit on grid dimension y of the plain kernels: fewer than 65536 of them)
+  if ((long long)T * (d > E ? d : E) >= (1ll << 40) || T >= (1 << 22)) return MOE_EUNSUPPORTED;
   if ((long long)d * 256 >= (1ll << 31) || (long long)d * E >= (1ll << 31)) return MOE_EUNSUPPORTED;
   return MOE_OK;
 }

@@ -144,15 +144,16 @@ __global__ void reduce_chunks(const float* __restrict__ partial, int chunks, siz
 
 // dx[t,c] (=|+=) sum_e dl[t,e] * Wr[c,e] for a small number of experts (the plain path's router term of dx):
 // one thread per 4 consecutive columns c, whose 4*E weights are contiguous in memory; the token's
-// dlogits row sits in LDS.  grid = (column groups, tokens).
+// dlogits row sits in LDS.  1-D grid: block = (token, group of 1024 columns), column group fastest.
 template <typename TW>
 __global__ __launch_bounds__(256) void router_dx_small_e(const float* __restrict__ dl, const TW* __restrict__ wr,
-                                                        TW* __restrict__ dx, int d, int E, int beta) {
+                                                        TW* __restrict__ dx, int d, int E, int beta, int col_groups) {
   __shared__ float row[MOE_MAX_EXPERTS];
-  const int t = blockIdx.y;
+  const int t = blockIdx.x / col_groups;
+  const int cg = blockIdx.x - t * col_groups;
   for (int e = threadIdx.x; e < E; e += 256) row[e] = dl[(size_t)t * E + e];
   __syncthreads();
-  const int c0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const int c0 = (cg * 256 + threadIdx.x) * 4;
   if (c0 >= d) return;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -524,11 +525,13 @@ int launch_router_bwd(const void* x, const void* wr, const float* dlogits, int d
     ProfScope prof(MOE_K_ROUTER_DX, s);
     if (E <= 64) {
       // a handful of experts: per-token dot products against contiguous weight rows
-      dim3 grid(tiles(d, 1024), T), blk(256);
+      const int col_groups = tiles(d, 1024);
+      if ((long long)col_groups * T >= (1ll << 31)) return MOE_EUNSUPPORTED;
+      dim3 grid((unsigned)(col_groups * T)), blk(256);
       if (dtype == MOE_BF16)
-        hipLaunchKernelGGL((router_dx_small_e<bf16_t>), grid, blk, 0, s, dlogits, (const bf16_t*)wr, (bf16_t*)dx, d, E, dx_acc);
+        hipLaunchKernelGGL((router_dx_small_e<bf16_t>), grid, blk, 0, s, dlogits, (const bf16_t*)wr, (bf16_t*)dx, d, E, dx_acc, col_groups);
       else
-        hipLaunchKernelGGL((router_dx_small_e<float>), grid, blk, 0, s, dlogits, (const float*)wr, (float*)dx, d, E, dx_acc);
+        hipLaunchKernelGGL((router_dx_small_e<float>), grid, blk, 0, s, dlogits, (const float*)wr, (float*)dx, d, E, dx_acc, col_groups);
     } else {
       // dx[t,n] (+)= sum_e dl[t,e] * Wr[n,e] : B(k = e, n) = Wr[n*E + e]
       dim3 grid(tiles(d, TN), tiles(T, TM)), blk(256);

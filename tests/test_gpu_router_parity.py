@@ -187,3 +187,23 @@ def test_trainable_gate_full_size_sampled():
     assert rel_err(host(dwr)[:, J], dwr_ref) < 2e-2
     _, dx_ref = O.router_bwd(x[rows], wr, dl[rows])
     assert rel_err(host(dx)[rows], dx_ref) < 2e-2
+
+
+def test_router_calls_with_more_tokens_than_one_grid_dimension_holds():
+    """T > 65535 with a handful of experts (the plain kernels): every launch shape must fit the grid limits."""
+    T, d, E = 70000, 64, 8
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    wr = (rng.standard_normal((d, E)) * d ** -0.5).astype(np.float32)
+    dl = rng.standard_normal((T, E)).astype(np.float32)
+    xd, wrd, dld = torch.from_numpy(x).cuda(), torch.from_numpy(wr).cuda(), torch.from_numpy(dl).cuda()
+    ws = torch.empty(B.moe_workspace_bytes(B.WS_ROUTER, B.MOE_F32, T, 2, d, 64, E, 0), dtype=torch.uint8, device="cuda")
+    logits = torch.full((T, E), 7.0, device="cuda")
+    B.moe_router_fwd(xd, wrd, logits, ws)
+    dwr = torch.full((d, E), 7.0, device="cuda"); dx = torch.full((T, d), 7.0, device="cuda")
+    B.moe_router_bwd(xd, wrd, dld, dwr, False, dx, False, ws)
+    torch.cuda.synchronize()
+    assert rel_err(host(logits), O.router_logits(x, wr)) < 1e-5
+    dwr_ref, dx_ref = O.router_bwd(x, wr, dl)
+    assert rel_err(host(dwr), dwr_ref) < 1e-5
+    assert rel_err(host(dx), dx_ref) < 1e-5
