@@ -726,18 +726,41 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     // row-major so that global accesses are 16 bytes per lane and 128 bytes per row segment.
     // A slab is private to its wavefront and LDS executes a wavefront's accesses in order, so
     // no workgroup barrier is needed between the writes and the reads.
-    // (two instances: a piece of a cut expert stores fp32 partial tiles, every other tile the final result)
-    auto epilogue = [&](auto partial_tag) {
+    // (three instances: a piece of a cut expert stores fp32 partial tiles, every other tile the final
+    // result, either overwriting or adding to what is there; adding is an instance of its own so that
+    // the loads of the old values are unconditional and stay where they are issued)
+    auto epilogue = [&](auto partial_tag, auto rmw_tag) {
     constexpr bool PARTIAL = decltype(partial_tag)::value != 0;
+    constexpr bool RMW_TAG = decltype(rmw_tag)::value != 0;
     float* stage = reinterpret_cast<float*>(smem + STAGING_OFF) + wave * (STAGING_WAVE_BYTES / 4);
     const int acc_col = lane & 31, acc_rg = lane >> 5;
     if (TR::DUAL) {
       // slab = 8 rows x 128 columns: both halves of a dual tile, so that a lane holds h1 and h3
       // (or dW1 and dW3) of the same position.  lanes: 8 per row (8 columns each).
       const int c8 = lane & 7, rl = lane >> 3;
+      // WGD adding to existing gradients: the old values of a slab are fetched C_AHEAD slabs
+      // before they are needed (clamped addresses), so that the read-modify-write does not
+      // wait for memory once per slab
+      constexpr int C_AHEAD = 3;
+      constexpr bool rmw = MODE == WGD && !PARTIAL && RMW_TAG;
+      uint4 old0[C_AHEAD + 1], old1[C_AHEAD + 1];
+      auto old_fetch = [&](int sl) {
+        int grow = ep_row0 + wm * 128 + (sl >> 2) * 32 + 8 * (sl & 3) + rl;
+        int gcol = ep_n0 + wn * 64 + c8 * 8;
+        if (grow > ep_row_end - 1) grow = ep_row_end - 1;
+        if (gcol > p.N - 8) gcol = p.N - 8;
+        const size_t idx = (size_t)ep_e * p.c_es + (size_t)grow * p.ldc + gcol;
+        old0[sl % (C_AHEAD + 1)] = *reinterpret_cast<const uint4*>(p.C0 + idx);
+        old1[sl % (C_AHEAD + 1)] = *reinterpret_cast<const uint4*>(p.C1 + idx);
+      };
+      if (rmw) {
+#pragma unroll
+        for (int sl = 0; sl < C_AHEAD; ++sl) old_fetch(sl);
+      }
 #pragma unroll
       for (int sl = 0; sl < 16; ++sl) {
         const int mi = sl >> 2, g = sl & 3;
+        if (rmw && sl + C_AHEAD < 16) old_fetch(sl + C_AHEAD);
 #pragma unroll
         for (int nj = 0; nj < 4; ++nj)
 #pragma unroll
@@ -780,8 +803,8 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
             const size_t idx = (size_t)ep_e * p.c_es + (size_t)grow * p.ldc + gcol;
             bf16_t* c0 = p.C0 + idx;
             bf16_t* c1 = p.C1 + idx;
-            if (p.accumulate) {
-              uint4 q0 = *reinterpret_cast<const uint4*>(c0), q1 = *reinterpret_cast<const uint4*>(c1);
+            if (rmw) {
+              const uint4 q0 = old0[sl % (C_AHEAD + 1)], q1 = old1[sl % (C_AHEAD + 1)];
               const uint32_t* u0 = reinterpret_cast<const uint32_t*>(&q0);
               const uint32_t* u1 = reinterpret_cast<const uint32_t*>(&q1);
 #pragma unroll
@@ -824,14 +847,33 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
           pre3[sl % (DA_AHEAD + 1)][pass] = *reinterpret_cast<const uint4*>(p.H3 + idx);
         }
       };
+      // WG and the router's dx adding to existing gradients: the same, with the old values
+      constexpr bool rmw = (MODE == WG || MODE == RX) && !PARTIAL && RMW_TAG;
+      auto old_fetch = [&](int sl) {
+        const int mi = sl >> 2, h = (sl >> 1) & 1, np = sl & 1;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+          int grow = ep_row0 + wm * 128 + mi * 32 + 16 * h + pass * 8 + (lane >> 3);
+          int gcol = ep_n0 + wn * 128 + np * 64 + c8 * 8;
+          if (grow > ep_row_end - 1) grow = ep_row_end - 1;
+          if (gcol > p.N - 8) gcol = p.N - 8;
+          const size_t idx = (MODE == WG ? (size_t)ep_e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
+          pre1[sl % (DA_AHEAD + 1)][pass] = *reinterpret_cast<const uint4*>(p.C0 + idx);
+        }
+      };
       if (MODE == DA) {
 #pragma unroll
         for (int sl = 0; sl < DA_AHEAD; ++sl) da_fetch(sl);
+      }
+      if (rmw) {
+#pragma unroll
+        for (int sl = 0; sl < DA_AHEAD; ++sl) old_fetch(sl);
       }
 #pragma unroll
       for (int sl = 0; sl < 16; ++sl) {
         const int mi = sl >> 2, h = (sl >> 1) & 1, np = sl & 1;
         if (MODE == DA && sl + DA_AHEAD < 16) da_fetch(sl + DA_AHEAD);
+        if (rmw && sl + DA_AHEAD < 16) old_fetch(sl + DA_AHEAD);
 #pragma unroll
         for (int gg = 0; gg < 2; ++gg)
 #pragma unroll
@@ -894,8 +936,8 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
             } else {
               const size_t idx = (MODE == WG ? (size_t)ep_e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
               bf16_t* c0 = p.C0 + idx;
-              if ((MODE == WG || MODE == RX) && p.accumulate) {
-                uint4 q0 = *reinterpret_cast<const uint4*>(c0);
+              if (rmw) {
+                const uint4 q0 = pre1[sl % (DA_AHEAD + 1)][pass];
                 const uint32_t* u0 = reinterpret_cast<const uint32_t*>(&q0);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) { x[2 * i] += bf16lo(u0[i]); x[2 * i + 1] += bf16hi(u0[i]); }
@@ -911,8 +953,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       }
     }
     };
-    if ((MODE == WG || MODE == WGD) && ep_piece >= 0) epilogue(IntC<1>{});
-    else epilogue(IntC<0>{});
+    if ((MODE == WG || MODE == WGD) && ep_piece >= 0) epilogue(IntC<1>{}, IntC<0>{});
+    else if ((MODE == WG || MODE == WGD || MODE == RX) && p.accumulate) epilogue(IntC<0>{}, IntC<1>{});
+    else epilogue(IntC<0>{}, IntC<0>{});
   }
 }
 

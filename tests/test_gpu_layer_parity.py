@@ -51,8 +51,14 @@ def test_layer_forward_backward(wl):
     print({k: f"{v:.2e}" for k, v in errs.items()}, "counts", fw["counts"].tolist(), flush=True)
 
 
-def test_accumulate_adds_to_existing_gradients():
-    wl = W.QWEN.scaled(name="qwen-acc", T=4096, d=128, f=128, zipf_s=2.0)      # includes experts cut along the rows
+@pytest.mark.parametrize("wl", [
+    W.QWEN.scaled(name="qwen-acc", T=4096, d=128, f=128, zipf_s=2.0),      # includes experts cut along the rows
+    # gradient tiles with tails in both directions and several full tiles beside them: the old
+    # values are fetched ahead of their slab with clamped addresses
+    W.DSV3.scaled(name="wide-tail-acc", T=1500, d=320, f=448, E=64, e_lo=8, e_cnt=8, k=6),
+    W.MIXTRAL.scaled(name="multi-tile-acc", T=1024, d=768, f=512, E=4, e_cnt=4, k=2),
+], ids=lambda w: w.name)
+def test_accumulate_adds_to_existing_gradients(wl):
     inp = make_inputs(wl)
     fw, bw = oracle_layer(wl, inp)
     dev, buf = gpu_layer(wl, inp)
