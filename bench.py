@@ -379,7 +379,7 @@ def router_row(B, C, W, torch, wl, dev, buf, R, U, b, reps=10):
         ms, n = B.moe_profile_read(name)
         if not n:
             continue
-        avg = ms / n
+        avg = ms / reps             # per call: a call may consist of several launches (rounding, GEMM, reduction)
         out[name] = dict(avg_ms=avg)
         if name in ("router_fwd", "router_dw", "router_dx"):
             out[name]["tflops"] = gemm_flop / (avg * 1e-3) / 1e12

@@ -96,6 +96,10 @@ struct GArgs {
   int M;                                  // WG/WGD: rows of the output (d or f)
   int N;                                  // output columns (per half for dual tiles)
   int K;                                  // contraction length per segment (ragged-M modes)
+  // RL only: the contraction is cut into ksplit ranges of K columns each (the last one may be
+  // shorter; k_total columns in all); range j writes its fp32 tile to F0 + j * c_es and a
+  // separate pass adds the ranges up.  0 or 1: not cut.
+  int ksplit, k_total;
   int accumulate;
   int save_h;
 };
@@ -260,7 +264,9 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   // ---- tile list.  Experts are taken heaviest first (ties by id), so that the cheap tiles
   // come last and even out the end of the schedule.  position -> expert in order[];
   // tile_start[pos] = number of tiles before that position (ragged-M modes).
-  const int n_tiles_n = (p.N + TR::BN_EFF - 1) / TR::BN_EFF;
+  // (RL: the ranges of a cut contraction are listed like further column tiles)
+  const int n_tiles_cols = (p.N + TR::BN_EFF - 1) / TR::BN_EFF;
+  const int n_tiles_n = MODE == RL && p.ksplit > 1 ? n_tiles_cols * p.ksplit : n_tiles_cols;
   int total;
   int wg_tiles_per_e = 0, wg_mt = 0;
   for (int e = tid; e <= e_cnt; e += NT) {
@@ -382,6 +388,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   // ---- state of the tile whose k loop runs next (written by next_tile)
   int e = 0, lo = 0, hi = 0, n0 = 0;
   int piece = -1;         // ragged-K modes: index of the fp32 partial tile to write, or -1
+  int krange = 0;         // RL: which range of a cut contraction
   int nk0 = 0, nk = 0;    // k-tiles in segment 0 / in total
   int row0 = 0;           // first output row (global row for ragged-M, i for the weight gradients)
   int row_end = 0;        // one past the last valid output row
@@ -499,6 +506,10 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
       nt = in_band / band_rows;
       mt = band * 8 + (in_band - nt * band_rows);
     }
+    if (MODE == RL) {
+      krange = nt / n_tiles_cols;
+      nt -= krange * n_tiles_cols;
+    }
     n0 = nt * TR::BN_EFF;
     if (TR::RAGGED_K) {
       row0 = mt * BM;
@@ -509,10 +520,11 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     } else {
       row0 = lo + mt * BM;
       row_end = hi;
-      nk0 = p.K / BK;
+      const size_t kfirst = MODE == RL ? (size_t)krange * p.K : 0;      // first column of this tile's range
+      nk0 = (MODE == RL && p.ksplit > 1 ? min(p.K, p.k_total - krange * p.K) : p.K) / BK;
       nk = MODE == DX ? 2 * nk0 : nk0;
-      ia_kp.setup(p.A0 + (size_t)row0 * p.lda, p.lda, hi - row0, wave, lane);
-      if (TR::B_TRANS) ib_tr.setup(p.B0 + (size_t)e * p.b_es, p.B1 + (size_t)e * p.b_es, TR::DUAL, p.ldb, n0, p.N, wave, lane);
+      ia_kp.setup(p.A0 + (size_t)row0 * p.lda + kfirst, p.lda, hi - row0, wave, lane);
+      if (TR::B_TRANS) ib_tr.setup(p.B0 + (size_t)e * p.b_es + kfirst * p.ldb, p.B1 + (size_t)e * p.b_es, TR::DUAL, p.ldb, n0, p.N, wave, lane);
       else ib_kc.setup(p.B0 + (size_t)e * p.b_es + (size_t)n0 * p.ldb, p.ldb, p.N - n0, wave, lane);
     }
     if (nk > 0) {
@@ -717,7 +729,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
     __syncthreads();
 
     // the ring is free: decode the next tile and start its first loads, then store this one
-    const int ep_e = e, ep_row0 = row0, ep_row_end = row_end, ep_n0 = n0, ep_piece = piece;
+    const int ep_e = e, ep_row0 = row0, ep_row_end = row_end, ep_n0 = n0, ep_piece = piece, ep_krange = krange;
     have = next_tile();
 
     // ---------------------------------------------------------------- epilogue
@@ -930,7 +942,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
               *reinterpret_cast<float4*>(c0) = make_float4(x[0], x[1], x[2], x[3]);
               *reinterpret_cast<float4*>(c0 + 4) = make_float4(x[4], x[5], x[6], x[7]);
             } else if (MODE == RL || MODE == RW) {
-              float* c0 = p.F0 + (MODE == RW ? (size_t)ep_e * p.c_es : (size_t)0) + (size_t)grow * p.ldc + gcol;
+              float* c0 = p.F0 + (size_t)(MODE == RW ? ep_e : ep_krange) * p.c_es + (size_t)grow * p.ldc + gcol;
               *reinterpret_cast<float4*>(c0) = make_float4(x[0], x[1], x[2], x[3]);
               *reinterpret_cast<float4*>(c0 + 4) = make_float4(x[4], x[5], x[6], x[7]);
             } else {
@@ -1136,25 +1148,56 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
 
 // ---- trainable router on the matrix cores (bf16, E % 64 == 0, d % 64 == 0) ----------------
 // ws layout: [0,256) ticket counters; then dl as bf16 [T,E]; then the fp32 chunk sums [S,d,E].
+// Into how many chunks of tokens the router's weight gradient is cut: the split whose schedule is
+// shortest, counted in k-tiles per workgroup: rounds of the chip's CUs times (k-tiles per chunk +
+// what a tile costs besides its k loop, about 16 k-tiles for its first loads and its fp32 stores).
+constexpr int SPLIT_OVERHEAD_KTILES = 16;
 int router_dw_splits(int T, int d, int E) {
-  const int tiles = ((d + BM - 1) / BM) * ((E + BN - 1) / BN);
-  int s = (device_cu_count() + tiles - 1) / tiles;
+  const long long tiles = (long long)((d + BM - 1) / BM) * ((E + BN - 1) / BN);
+  const int cus = device_cu_count();
   const int max_by_rows = (T + 4 * BK - 1) / (4 * BK);      // at least four k-tiles per chunk
-  if (s > max_by_rows) s = max_by_rows;
-  if (s > 32) s = 32;
-  return s < 1 ? 1 : s;
+  int best = 1;
+  long long best_cost = -1;
+  for (int s = 1; s <= 32 && s <= max_by_rows; ++s) {
+    const long long rounds = (tiles * s + cus - 1) / cus;
+    const long long cost = rounds * (((T + s - 1) / s + BK - 1) / BK + SPLIT_OVERHEAD_KTILES);
+    if (best_cost < 0 || cost < best_cost) { best = s; best_cost = cost; }
+  }
+  return best;
 }
 
-int launch_router_fwd_bf16(const void* x, const void* wr, int T, int d, int E, float* logits, int32_t* sched,
-                           hipStream_t s) {
+// Into how many ranges the router's forward GEMM cuts its contraction over d: with few experts
+// the [T, E] logits are fewer tiles than the chip has CUs, so each tile's k loop is shared out.
+// The same cost model as above, in pairs of k-tiles (a range is a whole number of pairs).
+int router_fwd_splits(int T, int d, int E) {
+  const long long tiles = (long long)((T + BM - 1) / BM) * ((E + BN - 1) / BN);
+  const int cus = device_cu_count();
+  const int pairs = d / (2 * BK);
+  int best = 1;
+  long long best_cost = -1;
+  for (int s = 1; s <= 8 && s <= pairs / 4; ++s) {
+    const long long rounds = (tiles * s + cus - 1) / cus;
+    const long long cost = rounds * (2 * ((pairs + s - 1) / s) + SPLIT_OVERHEAD_KTILES);
+    if (best_cost < 0 || cost < best_cost) { best = s; best_cost = cost; }
+  }
+  // no empty range: as many ranges as the rounded-up range length needs
+  const int per = (pairs + best - 1) / best;
+  return (pairs + per - 1) / per;
+}
+
+// partials: fp32 [splits, T, E] when the contraction is cut (splits > 1), else unused; the caller adds them up
+int launch_router_fwd_bf16(const void* x, const void* wr, int T, int d, int E, float* logits, float* partials,
+                           int splits, int32_t* sched, hipStream_t s) {
   if (T == 0) return MOE_OK;
   hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, sched, 8);
   HIP_CHECK_LAUNCH();
   GArgs g = {};
   g.A0 = g.A1 = (const bf16_t*)x; g.lda = d;
   g.B0 = g.B1 = (const bf16_t*)wr; g.ldb = E; g.b_es = 0;
-  g.F0 = logits; g.ldc = E;
-  g.off = nullptr; g.rows = T; g.chunk = T; g.sched = sched; g.e_cnt = 1; g.N = E; g.K = d;
+  g.F0 = splits > 1 ? partials : logits; g.ldc = E; g.c_es = (long)T * E;
+  g.off = nullptr; g.rows = T; g.chunk = T; g.sched = sched; g.e_cnt = 1; g.N = E;
+  const int pairs = d / (2 * BK);
+  g.ksplit = splits; g.k_total = d; g.K = splits > 1 ? (pairs + splits - 1) / splits * 2 * BK : d;
   return launch_gg<RL>(g, s);
 }
 

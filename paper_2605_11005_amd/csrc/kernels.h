@@ -48,8 +48,9 @@ int launch_gate_bwd(const float* logits, const int32_t* topk_idx, const float* d
 int launch_router_bwd(const void* x, const void* wr, const float* dlogits, int dtype, int T, int d, int E, void* dwr,
                       int dwr_acc, void* dx, int dx_acc, void* ws, hipStream_t s);
 int router_dw_splits(int T, int d, int E);
-int launch_router_fwd_bf16(const void* x, const void* wr, int T, int d, int E, float* logits, int32_t* sched,
-                           hipStream_t s);
+int router_fwd_splits(int T, int d, int E);
+int launch_router_fwd_bf16(const void* x, const void* wr, int T, int d, int E, float* logits, float* partials,
+                           int splits, int32_t* sched, hipStream_t s);
 int launch_router_dw_bf16(const void* x, const void* dl_bf16, int T, int d, int E, float* partials, int splits,
                           int32_t* sched, hipStream_t s);
 int launch_router_dx_bf16(const void* dl_bf16, const void* wr, int T, int d, int E, void* dx, int accumulate,

@@ -408,8 +408,12 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 size_t router_ws_bytes(int dtype, int T, int d, int E) {
   size_t b = 256;                                           // ticket counters
   if (mfma_shape(dtype, T, d, E)) {
-    b += align256((size_t)T * E * 2);                       // dlogits rounded to bf16
-    b += align256((size_t)router_dw_splits(T, d, E) * d * E * 4);
+    // backward: dlogits rounded to bf16 + the chunk sums of dWr; forward: the logits of each range
+    // of a cut contraction (the two calls use the same bytes one after the other)
+    const size_t bwd = align256((size_t)T * E * 2) + align256((size_t)router_dw_splits(T, d, E) * d * E * 4);
+    const int fs = router_fwd_splits(T, d, E);
+    const size_t fwd = fs > 1 ? align256((size_t)fs * T * E * 4) : 0;
+    b += bwd > fwd ? bwd : fwd;
   } else {
     b += align256((size_t)valu_splits(T, d, E) * d * E * 4);
   }
@@ -419,7 +423,17 @@ size_t router_ws_bytes(int dtype, int T, int d, int E) {
 int launch_router_fwd(const void* x, const void* wr, int dtype, int T, int d, int E, float* logits, void* ws,
                       hipStream_t s) {
   if (T == 0) return MOE_OK;
-  if (mfma_shape(dtype, T, d, E)) return launch_router_fwd_bf16(x, wr, T, d, E, logits, (int32_t*)ws, s);
+  if (mfma_shape(dtype, T, d, E)) {
+    const int splits = router_fwd_splits(T, d, E);
+    float* partial = (float*)((char*)ws + 256);
+    int rc = launch_router_fwd_bf16(x, wr, T, d, E, logits, partial, splits, (int32_t*)ws, s);
+    if (rc || splits == 1) return rc;
+    ProfScope prof(MOE_K_ROUTER_FWD, s);
+    hipLaunchKernelGGL((reduce_chunks<float>), dim3(device_cu_count() * 4), dim3(256), 0, s, partial, splits, (size_t)T * E,
+                       logits, 0);
+    HIP_CHECK_LAUNCH();
+    return MOE_OK;
+  }
   ProfScope prof(MOE_K_ROUTER_FWD, s);
   if (E <= 64) {
     if (dtype == MOE_BF16)
@@ -490,11 +504,15 @@ int launch_router_bwd(const void* x, const void* wr, const float* dlogits, int d
     bf16_t* dlb = (bf16_t*)base;
     float* partial = (float*)(base + align256((size_t)T * E * 2));
     if ((rc = launch_zero_words(sched, 16, s))) return rc;
-    hipLaunchKernelGGL(round_to_bf16, dim3(red_blocks), dim3(256), 0, s, dlogits, dlb, (size_t)T * E);
-    HIP_CHECK_LAUNCH();
+    {
+      ProfScope prof(dwr ? MOE_K_ROUTER_DW : MOE_K_ROUTER_DX, s);
+      hipLaunchKernelGGL(round_to_bf16, dim3(red_blocks), dim3(256), 0, s, dlogits, dlb, (size_t)T * E);
+      HIP_CHECK_LAUNCH();
+    }
     if (dwr) {
       const int splits = router_dw_splits(T, d, E);
       if ((rc = launch_router_dw_bf16(x, dlb, T, d, E, partial, splits, sched, s))) return rc;
+      ProfScope prof(MOE_K_ROUTER_DW, s);
       hipLaunchKernelGGL((reduce_chunks<bf16_t>), dim3(red_blocks), dim3(256), 0, s, partial, splits, n_w, (bf16_t*)dwr,
                          dwr_acc);
       HIP_CHECK_LAUNCH();

@@ -27,6 +27,9 @@ CASES = [
     W.DSV3.scaled(name="dsv3-small-router", T=4096, d=512, f=256),                 # E = 256, sigmoid gate
     W.DSV3.scaled(name="ragged-router", T=1500, d=320, f=448, E=96, e_lo=8, e_cnt=8, k=6),      # tails in every dimension
     W.QWEN.scaled(name="softmax-router", gate_mode=W.GATE_SOFTMAX, T=777, d=128, f=64, E=160, e_lo=32, e_cnt=64, k=4),
+    # few logit tiles and a long contraction: the router GEMM cuts d into five ranges of 5, 5, 5, 5 and 3 pairs of
+    # k-tiles and adds their fp32 tiles up; the token count leaves a ragged last row tile
+    W.QWEN.scaled(name="cut-contraction-router", T=1000, d=1472, f=64, E=128, e_lo=16, e_cnt=16, k=4),
 ]
 
 
