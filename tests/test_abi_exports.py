@@ -52,6 +52,31 @@ def test_error_strings_and_workspace_sizes(lib):
     assert B.moe_workspace_bytes(B.WS_DISPATCH, B.MOE_BF16, 1024, 8, 64, 128, 4, 1000) >= 16 * 4 * 4
 
 
+def test_router_workspace_reflects_how_the_router_gemms_are_cut(lib):
+    """The router workspace is the larger of what the forward (fp32 logits per range of a cut
+    contraction) and the backward (dlogits as bf16 + fp32 chunk sums of dWr) need; its size shows
+    the cuts the host chose.  Counted for 256 CUs (what a host without a GPU assumes, and what the
+    chip has): rounds of the CUs x (k-tiles per work item + 16)."""
+    al = lambda v: (v + 255) // 256 * 256
+    ws = lambda T, d, E: B.moe_workspace_bytes(B.WS_ROUTER, B.MOE_BF16, T, 8, d, 2048, E, 0)
+    # T = 32768, d = 7168, E = 256: 128 logit tiles -> two ranges of d (one round); 28 dWr tiles -> 9 token
+    # chunks (252 work items, one round; 10 chunks would take two rounds)
+    T, d, E = 32768, 7168, 256
+    assert ws(T, d, E) == 256 + max(al(T * E * 2) + al(9 * d * E * 4), al(2 * T * E * 4))
+    # 65536 tokens: 256 logit tiles fill the chip, the contraction stays whole; dWr as before
+    T = 65536
+    assert ws(T, d, E) == 256 + al(T * E * 2) + al(9 * d * E * 4)
+    # a short contraction (four pairs of k-tiles) is never cut; 1 x 1 dWr tile over 2048 tokens: at least four
+    # k-tiles per chunk bounds the chunks at 16
+    T, d, E = 2048, 256, 128
+    assert ws(T, d, E) == 256 + al(T * E * 2) + al(16 * d * E * 4)
+    # 23 pairs of k-tiles, 128 logit tiles: two ranges (12 and 11 pairs; three would need a second round);
+    # 6 dWr tiles: 32 token chunks (the most allowed) still fit one round
+    T, d, E = 32768, 1472, 256
+    assert ws(T, d, E) == 256 + max(al(T * E * 2) + al(32 * d * E * 4), al(2 * T * E * 4))
+    assert al(2 * T * E * 4) > al(T * E * 2) + al(32 * d * E * 4)          # (the forward's need decides here)
+
+
 def test_host_validation_rejects_before_launch(lib):
     """Only calls that fail validation are made here (no GPU needed: nothing is launched)."""
     P = ctypes.c_void_p
