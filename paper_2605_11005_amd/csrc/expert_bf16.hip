@@ -381,7 +381,6 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   const int G = gridDim.x;
   const int n_queues = (G % 8) == 0 ? 8 : 1;
   int queue = blockIdx.x % n_queues;       // the queue this workgroup currently draws from
-  int exhausted = 0;                       // queues found empty so far
   int pos_hint = 0;                        // list position of the last decoded tile
   const uint32_t smem_base = lds_addr(smem);
 
@@ -436,7 +435,7 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   // c mod 8 (workgroup b runs on XCD b mod 8), whose workgroups draw tiles from it in order
   // through one atomic counter per XCD.  Ticket q of XCD x is tile 32*(8*(q/32) + x) + q%32.
   // The ticket for the next tile is drawn near the end of the current k loop.  A workgroup whose
-  // queue has run dry moves on to the next XCD's queue.
+  // queue has run dry draws from the next XCD's queue that still has tiles.
   //
   // next_tile: takes the ticket waiting in *next_q, decodes it into the tile state above and
   // starts the loads of that tile's first k-tiles.  The tile ring must be free when it is
@@ -445,16 +444,41 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   auto next_tile = [&]() -> bool {
     int L;
     while (true) {
-      const int q = __builtin_amdgcn_readfirstlane(*next_q);
+      const int q = __builtin_amdgcn_readfirstlane(next_q[0]);
       L = 32 * (n_queues * (q >> 5) + queue) + (q & 31);
       if (L < total) break;                  // (the slot is next written after a whole k loop of barriers)
-      // tickets only grow, so this queue is finished: help the next XCD's queue (work stealing
-      // at the tail of the schedule), stop once every queue has been seen empty
-      if (++exhausted == n_queues) return false;
-      queue = (queue + 1) % n_queues;
+      // Tickets only grow, so this queue is finished, and so is every queue whose counter has passed
+      // its last ticket.  All counters are looked at in one round trip (an atomic add of zero, one lane
+      // per queue): when none is open the workgroup is done; otherwise it draws from the first open
+      // queue after its own (work stealing at the tail of the schedule) and, should others have emptied
+      // that queue in between, looks again.  Every failed draw means that others took tiles meanwhile,
+      // so the loop ends when the list does.
       __syncthreads();                       // everyone has read the ticket before it is replaced
-      if (tid == 0) *next_q = atomicAdd(p.sched + queue, 1);
+      if (wave == 0) {
+        int open = 0;
+        if (lane < n_queues) {
+          const int per_round = 32 * n_queues;
+          const int full = total / per_round;
+          int extra = total - full * per_round - 32 * lane;
+          extra = extra < 0 ? 0 : (extra > 32 ? 32 : extra);
+          open = atomicAdd(p.sched + lane, 0) < 32 * full + extra;
+        }
+        const unsigned all = (1u << n_queues) - 1u;
+        const unsigned m = (unsigned)__ballot(open) & all;
+        if (lane == 0) {
+          if (m == 0) {
+            next_q[0] = -1;
+          } else {
+            const unsigned rot = ((m >> (queue + 1)) | (m << (n_queues - queue - 1))) & all;
+            const int pick = (queue + 1 + __builtin_ctz(rot)) % n_queues;
+            next_q[1] = pick;
+            next_q[0] = atomicAdd(p.sched + pick, 1);
+          }
+        }
+      }
       __syncthreads();
+      if (__builtin_amdgcn_readfirstlane(next_q[0]) < 0) return false;
+      queue = __builtin_amdgcn_readfirstlane(next_q[1]);
     }
     // Within an expert, tiles are ordered in bands of 8 m-tiles, n-tile next, m-tile inside the
     // band fastest: 32 consecutive tiles (one chunk) then form an 8 x 4 block that shares 8 A
