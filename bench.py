@@ -24,7 +24,9 @@ HBM_PEAK_GBPS = 8000.0
 INFINITY_CACHE_BYTES = 256 << 20
 
 # useful FLOP per routed row, in units of d*f, of each grouped-GEMM kernel
-GEMM_FLOP_UNITS = dict(up=4, down=2, da=2, dx=4, wg=2, wgd=4)
+# units of R*d*f FLOP per launch; the backward runs GEMMs that do not depend on each other as one launch
+GEMM_FLOP_UNITS = dict(up=4, down=2, da=2, dx=4, wg=2, wgd=4, da_wg=4, dx_wgd=8)
+GEMM_KERNEL_NAMES = dict(da_wg="gg_pair<DA,WG>", dx_wgd="gg_pair<DX,WGD>")
 
 
 def main():
@@ -171,7 +173,8 @@ def run_workload(wl, steps, warmup, full, args):
     d, f, T, k = wl.d, wl.f, wl.T, wl.k
     flop_step = C.layer_flops(R, d, f)
     value = flop_step / (ms_per_step * 1e-3) / 1e12
-    # per step: the six grouped-GEMM launches plus the two partial-tile reductions of cut weight gradients
+    # per step: the grouped-GEMM launches (six GEMMs in four launches: dA with dW2, dX with dW1|dW3) plus the two
+    # partial-tile reductions of cut weight gradients
     gemm_ms = sum(kern[n]["avg_ms"] * kern[n]["launches"] for n in list(GEMM_FLOP_UNITS) + ["wgrad_reduce"] if n in kern) / steps
     for name, units in GEMM_FLOP_UNITS.items():
         if name in kern:
@@ -187,7 +190,7 @@ def run_workload(wl, steps, warmup, full, args):
     roofline = None
     if bf16:
         dom = max((n for n in GEMM_FLOP_UNITS if n in kern), key=lambda n: kern[n]["avg_ms"])
-        kname = f"gg_kernel<{dom.upper()}>"
+        kname = GEMM_KERNEL_NAMES.get(dom, f"gg_kernel<{dom.upper()}>")
         roofline = dict(kernel=kname, bound="mfma", achieved=kern[dom]["tflops"],
                         peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=kern[dom]["tflops"] / MFMA_BF16_PEAK_TFLOPS,
                         traffic=measured_traffic(wl.name, kname),

@@ -268,7 +268,12 @@ enum { MOE_K_ROUTE = 0, MOE_K_PLAN = 1, MOE_K_DISPATCH = 2, MOE_K_COMBINE = 3, M
        MOE_K_DOWN = 5, MOE_K_DA = 6, MOE_K_DX = 7, MOE_K_WG = 8, MOE_K_WGD = 9, MOE_K_ROUTER_FWD = 10,
        MOE_K_COMBINE_BWD = 11, MOE_K_GATE_BWD = 12, MOE_K_ROUTER_DW = 13, MOE_K_ROUTER_DX = 14,
        MOE_K_WGRAD_REDUCE = 15,   /* sum of the fp32 partial tiles of weight gradients cut along the rows */
-       MOE_K_COUNT = 16 };
+       /* bf16 backward: GEMMs that do not depend on each other may share a launch (the second fills
+        * the first one's tail): dA with dW2 when moe_expert_bwd is given the forward's a, dX with
+        * dW1|dW3, each when the capacity bound gives a workgroup at most a dozen tiles of the first.
+        * A shared launch is booked here and not under the single ids. */
+       MOE_K_DA_WG = 16, MOE_K_DX_WGD = 17,
+       MOE_K_COUNT = 18 };
 #define MOE_PROFILE_MAX_EVENTS 8192
 int moe_profile_enable(int on);
 int moe_profile_read(int kernel, double* total_ms /* host */, int* launches /* host */);

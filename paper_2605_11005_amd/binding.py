@@ -246,7 +246,7 @@ def moe_router_bwd(x, wr, dlogits, dwr, dwr_accumulate, dx, dx_accumulate, ws):
 
 
 KERNEL_IDS = dict(route=0, plan=1, dispatch=2, combine=3, up=4, down=5, da=6, dx=7, wg=8, wgd=9, router_fwd=10,
-                  combine_bwd=11, gate_bwd=12, router_dw=13, router_dx=14, wgrad_reduce=15)
+                  combine_bwd=11, gate_bwd=12, router_dw=13, router_dx=14, wgrad_reduce=15, da_wg=16, dx_wgd=17)
 
 
 def moe_profile_enable(on: bool):

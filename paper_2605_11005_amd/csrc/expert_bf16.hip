@@ -245,10 +245,12 @@ __device__ __forceinline__ bf16x8 lds_frag_tr(const char* p) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
+extern __shared__ __align__(16) char smem[];
+
+// One grouped GEMM from its set-up to its last tile, run by a persistent workgroup.
 template <int MODE>
-__global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
+__device__ __forceinline__ void gg_body(const GArgs& p) {
   using TR = Traits<MODE>;
-  extern __shared__ __align__(16) char smem[];
   int32_t* tile_start = reinterpret_cast<int32_t*>(smem + TILE_LDS);
   int32_t* offs = tile_start + (MOE_MAX_LOCAL + 1);      // LDS copy of the row offsets
   int32_t* split = offs + (MOE_MAX_LOCAL + 1);           // ragged-K modes: (first piece << 8) | pieces, by expert
@@ -995,6 +997,21 @@ __global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
   }
 }
 
+template <int MODE>
+__global__ __launch_bounds__(NT, 1) void gg_kernel(GArgs p) {
+  gg_body<MODE>(p);
+}
+
+// Two grouped GEMMs that do not depend on each other in one launch: a workgroup that finds no tile
+// of the first left goes on to the second at once, so the second fills the first one's tail (the
+// last round of whole tiles, in which most CUs would idle) and one launch boundary goes away.
+template <int M1, int M2>
+__global__ __launch_bounds__(NT, 1) void gg_pair(GArgs p1, GArgs p2) {
+  gg_body<M1>(p1);
+  __syncthreads();          // the first GEMM's scheduler tables in LDS are rewritten by the second's set-up
+  gg_body<M2>(p2);
+}
+
 __global__ void zero_words(int32_t* p, int n) {
   if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
 }
@@ -1065,6 +1082,23 @@ inline int32_t* sched_area(void* ws, size_t scratch_bytes) {
 
 constexpr size_t WGRAD_PLAN_BYTES = 2 * MOE_MAX_LOCAL * 4;
 
+template <int M1, int M2>
+int launch_pair(const GArgs& a, const GArgs& b, int prof_id, hipStream_t s) {
+  static bool attr_set[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_EHIP;
+  if (!attr_set[dev]) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gg_pair<M1, M2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            SMEM_BYTES) != hipSuccess)
+      return MOE_EHIP;
+    attr_set[dev] = true;
+  }
+  ProfScope prof(prof_id, s);
+  hipLaunchKernelGGL((gg_pair<M1, M2>), dim3(device_cu_count()), dim3(NT), SMEM_BYTES, s, a, b);
+  HIP_CHECK_LAUNCH();
+  return MOE_OK;
+}
+
 template <int MODE>
 int launch_gg(const GArgs& a, hipStream_t s) {
   // the LDS opt-in is a per-device attribute of the kernel
@@ -1124,43 +1158,67 @@ int launch_expert_bwd_bf16(const void* xp, const void* h1, const void* h3, const
   const long mn = (long)d * f;
   hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, sched, 32);
   HIP_CHECK_LAUNCH();
-  int rc;
-  if (cap > 0) {
-    GArgs g = {};   // dA = d_o W2^T, epilogue -> a, dH1, dH3
-    g.A0 = g.A1 = (const bf16_t*)d_o; g.lda = d;
-    g.B0 = g.B1 = (const bf16_t*)w2; g.ldb = d; g.b_es = (long)f * d;
-    g.C0 = a_in ? nullptr : a; g.C1 = dh1; g.C2 = dh3; g.ldc = f;
-    g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3;
-    g.off = offsets; g.sched = sched; g.e_cnt = e_cnt; g.N = f; g.K = d;
-    if ((rc = launch_gg<DA>(g, s))) return rc;
-    GArgs x = {};   // dxp = dH1 W1^T + dH3 W3^T
-    x.A0 = dh1; x.A1 = dh3; x.lda = f;
-    x.B0 = (const bf16_t*)w1; x.B1 = (const bf16_t*)w3; x.ldb = f; x.b_es = (long)d * f;
-    x.C0 = (bf16_t*)dxp; x.ldc = d;
-    x.off = offsets; x.sched = sched + 8; x.e_cnt = e_cnt; x.N = d; x.K = f;
-    if ((rc = launch_gg<DX>(x, s))) return rc;
-  }
-  GArgs w = {};     // dW2 = a^T d_o
+  GArgs g = {};   // dA = d_o W2^T, epilogue -> a, dH1, dH3
+  g.A0 = g.A1 = (const bf16_t*)d_o; g.lda = d;
+  g.B0 = g.B1 = (const bf16_t*)w2; g.ldb = d; g.b_es = (long)f * d;
+  g.C0 = a_in ? nullptr : a; g.C1 = dh1; g.C2 = dh3; g.ldc = f;
+  g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3;
+  g.off = offsets; g.sched = sched; g.e_cnt = e_cnt; g.N = f; g.K = d;
+  GArgs x = {};   // dxp = dH1 W1^T + dH3 W3^T
+  x.A0 = dh1; x.A1 = dh3; x.lda = f;
+  x.B0 = (const bf16_t*)w1; x.B1 = (const bf16_t*)w3; x.ldb = f; x.b_es = (long)d * f;
+  x.C0 = (bf16_t*)dxp; x.ldc = d;
+  x.off = offsets; x.sched = sched + 8; x.e_cnt = e_cnt; x.N = d; x.K = f;
+  GArgs w = {};   // dW2 = a^T d_o
   w.A0 = w.A1 = a_in ? (const bf16_t*)a_in : a; w.lda = f;
   w.B0 = w.B1 = (const bf16_t*)d_o; w.ldb = d;
   w.C0 = (bf16_t*)dw2; w.ldc = d; w.c_es = (long)f * d;
   w.off = offsets; w.sched = sched + 16; w.e_cnt = e_cnt; w.M = f; w.N = d; w.accumulate = accumulate;
   w.P0 = partials; w.p_stride = mn; w.split_budget = (int)(split_bytes / (mn * 4)); w.plan = plans;
-  if ((rc = launch_gg<WG>(w, s))) return rc;
+  GArgs v = {};   // dW1|dW3 = xp^T [dH1|dH3]
+  v.A0 = v.A1 = (const bf16_t*)xp; v.lda = d;
+  v.B0 = dh1; v.B1 = dh3; v.ldb = f;
+  v.C0 = (bf16_t*)dw1; v.C1 = (bf16_t*)dw3; v.ldc = f; v.c_es = (long)d * f;
+  v.off = offsets; v.sched = sched + 24; v.e_cnt = e_cnt; v.M = d; v.N = f; v.accumulate = accumulate;
+  v.P0 = partials; v.p_stride = 2 * mn; v.split_budget = (int)(split_bytes / (2 * mn * 4)); v.plan = plans + MOE_MAX_LOCAL;
+  // Order and pairing.  dW2 needs a and d_o, dX and dW1|dW3 need what dA's epilogue writes (dH1, dH3).  With the
+  // forward's a at hand dA and dW2 are independent, dX and dW1|dW3 always are, and independent GEMMs may share a
+  // launch (gg_pair).  That pays while the first GEMM's tail -- its last round of whole tiles -- is a visible part
+  // of it; the second GEMM's workgroups then start out of step, and the panels that the 32 workgroups of an XCD
+  // would share through their L2 while walking k together are fetched more often (a quarter more L2 misses
+  // measured).  Measured break-even: about a dozen rounds of tiles per workgroup in the first GEMM (a pair gains
+  // 2.5-4 % at 8-9 rounds and loses 1-2.5 % at 29-31), counted from the capacity bound since the row counts are
+  // on the device.  The fp32 partial tiles of cut experts are one buffer: dW2's are added up before dW1|dW3
+  // writes its own.
+  int rc;
   const int red_grid = 4 * device_cu_count();
+  const auto rounds = [&](int n_cols) {     // tiles of a ragged-M GEMM with n_cols output columns, per workgroup
+    const long long m_tiles = (cap + BM - 1) / BM + e_cnt / 2;
+    return m_tiles * ((n_cols + BN - 1) / BN) / device_cu_count();
+  };
+  constexpr int PAIR_MAX_ROUNDS = 12;
+  if (cap == 0) {            // no rows at all: only the gradients are written (zeros unless accumulating)
+    if ((rc = launch_gg<WG>(w, s))) return rc;
+  } else if (a_in && rounds(f) <= PAIR_MAX_ROUNDS) {
+    if ((rc = launch_pair<DA, WG>(g, w, MOE_K_DA_WG, s))) return rc;
+  } else {
+    if ((rc = launch_gg<DA>(g, s))) return rc;
+    if ((rc = launch_gg<WG>(w, s))) return rc;
+  }
   {
     ProfScope prof(MOE_K_WGRAD_REDUCE, s);
     hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans, e_cnt, partials, mn, mn, 1, (bf16_t*)dw2,
                        (bf16_t*)dw2, mn, accumulate);
   }
   HIP_CHECK_LAUNCH();
-  GArgs v = {};     // dW1|dW3 = xp^T [dH1|dH3]
-  v.A0 = v.A1 = (const bf16_t*)xp; v.lda = d;
-  v.B0 = dh1; v.B1 = dh3; v.ldb = f;
-  v.C0 = (bf16_t*)dw1; v.C1 = (bf16_t*)dw3; v.ldc = f; v.c_es = (long)d * f;
-  v.off = offsets; v.sched = sched + 24; v.e_cnt = e_cnt; v.M = d; v.N = f; v.accumulate = accumulate;
-  v.P0 = partials; v.p_stride = 2 * mn; v.split_budget = (int)(split_bytes / (2 * mn * 4)); v.plan = plans + MOE_MAX_LOCAL;
-  if ((rc = launch_gg<WGD>(v, s))) return rc;
+  if (cap == 0) {
+    if ((rc = launch_gg<WGD>(v, s))) return rc;
+  } else if (rounds(d) <= PAIR_MAX_ROUNDS) {
+    if ((rc = launch_pair<DX, WGD>(x, v, MOE_K_DX_WGD, s))) return rc;
+  } else {
+    if ((rc = launch_gg<DX>(x, s))) return rc;
+    if ((rc = launch_gg<WGD>(v, s))) return rc;
+  }
   {
     ProfScope prof(MOE_K_WGRAD_REDUCE, s);
     hipLaunchKernelGGL(wgrad_reduce, dim3(red_grid), dim3(256), 0, s, plans + MOE_MAX_LOCAL, e_cnt, partials, 2 * mn, mn, 2,
