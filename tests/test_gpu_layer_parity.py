@@ -71,6 +71,25 @@ def test_accumulate_adds_to_existing_gradients(wl):
         assert rel_err(host(t), 2.0 * b) < 1e-2
 
 
+def test_shared_and_separate_launches_give_the_same_bits():
+    """The backward lets GEMMs that do not depend on each other share a launch when the capacity bound
+    gives a workgroup few tiles of the first, and launches them one by one otherwise; which one runs
+    changes no arithmetic.  The same inputs with a tight and with a very loose capacity (1 and 21 rounds
+    of dA tiles per workgroup, 1 and 21 of dX) must give identical bits; the tight run is also held
+    to the oracle by the case list above (dsv3-small)."""
+    wl = W.DSV3.scaled(name="dsv3-pairing", T=4096, d=512, f=512)
+    inp = make_inputs(wl)
+    _, tight = gpu_layer(wl, inp)                                     # T*k = 32768 rows bound: shared launches
+    R = int(tight.offsets[-1].item())
+    _, loose = gpu_layer(wl, inp, cap=700000)                         # separate launches
+    assert int(loose.offsets[-1].item()) == R and R > 1000
+    for name in ("dw1", "dw3", "dw2"):
+        assert torch.equal(getattr(tight, name), getattr(loose, name)), name
+    for name in ("h1", "h3", "o", "dxp"):
+        assert torch.equal(getattr(tight, name)[:R], getattr(loose, name)[:R]), name
+    assert torch.equal(tight.dx, loose.dx) and torch.equal(tight.y, loose.y)
+
+
 def test_run_to_run_bit_stability():
     wl = W.DSV3.scaled(name="dsv3-stab", T=2048, d=256, f=128)
     inp = make_inputs(wl)
