@@ -71,6 +71,37 @@ def test_accumulate_adds_to_existing_gradients(wl):
         assert rel_err(host(t), 2.0 * b) < 1e-2
 
 
+def _random_cases(n, seed):
+    """Seeded draws of small shapes: odd token counts, every multiple-of-64 width up to 448, expert counts
+    and local slices of any size, all three gate modes, flat to very skewed popularity."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        bf16 = i % 4 != 3
+        E = int(rng.integers(1, 41))
+        e_cnt = int(rng.integers(1, E + 1))
+        e_lo = int(rng.integers(0, E - e_cnt + 1))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        step = 64 if bf16 else 4
+        d = int(rng.integers(1, 8 if bf16 else 40)) * step
+        f = int(rng.integers(1, 8 if bf16 else 40)) * step
+        base = W.DSV3 if bf16 else W.TINY
+        out.append(base.scaled(name=f"random-{seed}-{i}", T=int(rng.integers(1, 900)), d=d, f=f, E=E, e_lo=e_lo, e_cnt=e_cnt,
+                               k=k, gate_mode=int(rng.integers(0, 3)), routing="zipf", zipf_s=float(rng.choice([0.0, 1.0, 2.5])),
+                               dtype="bf16" if bf16 else "f32"))
+    return out
+
+
+@pytest.mark.parametrize("wl", _random_cases(16, 20260511), ids=lambda w: w.name)
+def test_random_small_shapes(wl):
+    print(f"case {wl.name} T={wl.T} d={wl.d} f={wl.f} E={wl.E} slice=[{wl.e_lo},{wl.e_lo + wl.e_cnt}) k={wl.k} "
+          f"gate={wl.gate_mode} zipf={wl.zipf_s} {wl.dtype}", flush=True)
+    inp = make_inputs(wl)
+    fw, bw = oracle_layer(wl, inp)
+    _, buf = gpu_layer(wl, inp)
+    check_layer(wl, inp, fw, bw, buf)
+
+
 def test_shared_and_separate_launches_give_the_same_bits():
     """The backward lets GEMMs that do not depend on each other share a launch when the capacity bound
     gives a workgroup few tiles of the first, and launches them one by one otherwise; which one runs
