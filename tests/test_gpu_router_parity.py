@@ -33,7 +33,22 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("wl", CASES, ids=lambda w: w.name)
+def _random_router_cases(n, seed):
+    """Seeded draws for the matrix-core router path (E and d multiples of 64): token counts with ragged
+    last tiles, contractions from one pair of k-tiles to 24 (cut into up to five ranges), any slice."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        E = 64 * int(rng.integers(1, 5))
+        e_cnt = int(rng.integers(1, 33))
+        e_lo = int(rng.integers(0, E - e_cnt + 1))
+        out.append(W.DSV3.scaled(name=f"random-router-{seed}-{i}", T=int(rng.integers(1, 2500)), d=64 * int(rng.integers(1, 25)),
+                                 f=64 * int(rng.integers(1, 3)), E=E, e_lo=e_lo, e_cnt=e_cnt, k=int(rng.integers(1, 9)),
+                                 gate_mode=int(rng.integers(0, 3)), zipf_s=float(rng.choice([0.0, 1.0]))))
+    return out
+
+
+@pytest.mark.parametrize("wl", CASES + _random_router_cases(6, 20260512), ids=lambda w: w.name)
 def test_trainable_gate_forward_backward(wl):
     print(f"case {wl.name} T={wl.T} d={wl.d} f={wl.f} E={wl.E} slice=[{wl.e_lo},{wl.e_lo + wl.e_cnt}) k={wl.k} "
           f"gate={wl.gate_mode} {wl.dtype}", flush=True)
